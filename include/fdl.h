@@ -1,0 +1,117 @@
+/*
+ * fdl -- fused dense-layer block for AMD MI355X (gfx950), C ABI.
+ *
+ *     Y = LayerNorm( GELU_erf( X W^T + b ) ) * gamma + beta          (forward)
+ *     (dX, dW, db, dgamma, dbeta) for an upstream gradient dY         (backward)
+ *
+ * Operator conventions follow the paper's task definitions (appendix "Robust
+ * Kernel Benchmark", linear backward task definition): the linear step is
+ * torch's F.linear, y = x W^T + b with W stored [out_features, in_features];
+ * the forward call keeps what backward needs; the backward call receives the
+ * upstream gradient plus the saved tensors and returns the gradient of every
+ * input.  A kernel counts as correct only if it reproduces the torch operator
+ * (appendix "Kernel Evaluation Environment"), hence GELU is the exact erf form,
+ * LayerNorm normalises over the last dimension with the biased variance, and
+ * eps sits inside the square root.
+ *
+ * All pointers except where noted are DEVICE pointers owned by the caller.
+ * Matrices are row-major and contiguous, with no padding between rows:
+ *   X [M,K]   W [N,K]   Y, Zsave, dY [M,N]   dX [M,K]   dW [N,K]
+ * and are stored in the type selected by `dt`.  Vectors b, gamma, beta, db,
+ * dgamma, dbeta [N] and mean, rstd [M] are always fp32.  Base pointers must be
+ * 16-byte aligned; row pitches need not be.
+ *
+ * The library allocates nothing and never synchronises: every call only
+ * enqueues kernels on `hip_stream` (a hipStream_t passed as void*; NULL is the
+ * default stream) and returns.  Scratch memory comes from the caller through
+ * `workspace` (device memory, 256-byte aligned, at least
+ * fdl_workspace_bytes(...) bytes, contents undefined before and after a call).
+ * Outputs are overwritten, never accumulated into.  Input and output buffers
+ * must not overlap.  Calls that share a workspace must be ordered on a stream.
+ *
+ * Errors are reported by return code; every argument check happens before any
+ * device call, so a rejected call has touched nothing.  FDL_ERR_LAUNCH reports
+ * a HIP launch error (hipGetLastError after the launches).
+ */
+#ifndef FDL_H_
+#define FDL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FDL_OK = 0,
+  FDL_ERR_NULL = 1,       /* a required pointer is NULL                           */
+  FDL_ERR_SHAPE = 2,      /* M, K or N < 1, or a product overflows the supported range */
+  FDL_ERR_DTYPE = 3,      /* dt is not a member of fdl_dtype                      */
+  FDL_ERR_EPS = 4,        /* eps is negative, NaN or infinite                     */
+  FDL_ERR_WORKSPACE = 5,  /* workspace is NULL or smaller than fdl_workspace_bytes */
+  FDL_ERR_ALIGN = 6,      /* a base pointer is not 16-byte aligned (workspace: 256) */
+  FDL_ERR_LAUNCH = 7      /* HIP reported an error when launching                 */
+} fdl_status;
+
+typedef enum {
+  FDL_F32 = 0,   /* matrices stored as fp32; contractions and reductions accumulate in fp64 */
+  FDL_BF16 = 1   /* matrices stored as bf16; contractions and reductions accumulate in fp32 */
+} fdl_dtype;
+
+/* Human-readable name of a status code (host pointer to a static string). */
+const char* fdl_status_string(fdl_status s);
+
+/*
+ * Bytes of device scratch that fdl_forward and fdl_backward need for this
+ * problem (the larger of the two, so one buffer serves both).  Returns 0 for
+ * an invalid dtype or shape.  Host-only: touches no device.
+ */
+size_t fdl_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N);
+
+/*
+ * Forward:  Z = X W^T + b;  A = GELU_erf(Z) = Z * Phi(Z);
+ *           mean_i = (1/N) sum_j A_ij;  var_i = (1/N) sum_j (A_ij - mean_i)^2;
+ *           rstd_i = (var_i + eps)^(-1/2);
+ *           Y_ij = (A_ij - mean_i) * rstd_i * gamma_j + beta_j.
+ * (Linear step: linear task definition in the appendix "Robust Kernel
+ * Benchmark"; LayerNorm as a two-step "row statistics, then normalise" pass:
+ * appendix "Highlighted CUDA Kernels: Analysis", LayerNorm forward.)
+ *
+ * in : X [M,K], W [N,K] (dt);  b, gamma, beta [N] fp32;  eps >= 0.
+ * out: Y [M,N] (dt);  Zsave [M,N] (dt) = Z rounded to dt, the pre-activation
+ *      kept for backward;  mean, rstd [M] fp32 = row statistics of
+ *      GELU_erf(Zsave) (i.e. of the stored, rounded pre-activation).
+ */
+fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+                       const void* X, const void* W,
+                       const float* b, const float* gamma, const float* beta, float eps,
+                       void* Y, void* Zsave, float* mean, float* rstd,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward, given dY [M,N] and the tensors saved by fdl_forward:
+ *   Ahat_ij = (GELU_erf(Z_ij) - mean_i) * rstd_i;     g_ij = dY_ij * gamma_j;
+ *   c1_i = (1/N) sum_j g_ij;    c2_i = (1/N) sum_j g_ij * Ahat_ij;
+ *   dA_ij = rstd_i * (g_ij - c1_i - Ahat_ij * c2_i);
+ *   dZ_ij = dA_ij * (Phi(Z_ij) + Z_ij * phi(Z_ij));
+ *   dbeta_j = sum_i dY_ij;   dgamma_j = sum_i dY_ij * Ahat_ij;   db_j = sum_i dZ_ij;
+ *   dX = dZ W   [M,K];       dW = dZ^T X   [N,K].
+ * (Gradient contract and the three linear-layer gradients: linear backward
+ * task definition and the "MNIST Linear Backward Kernel" listing's operator;
+ * recomputation of the activation from the saved pre-activation in backward:
+ * "MNIST Linear-ReLU Backward Kernel".)
+ *
+ * in : dY [M,N], X [M,K], W [N,K], Zsave [M,N] (dt);  gamma [N], mean, rstd [M] fp32.
+ * out: dX [M,K], dW [N,K] (dt);  db, dgamma, dbeta [N] fp32.
+ */
+fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+                        const void* dY, const void* X, const void* W, const float* gamma,
+                        const void* Zsave, const float* mean, const float* rstd,
+                        void* dX, void* dW, float* db, float* dgamma, float* dbeta,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDL_H_ */

@@ -1,0 +1,113 @@
+"""ctypes binding of libfdl.so: same names as the C ABI (include/fdl.h).
+
+Argument marshalling only: every arithmetic step runs inside the library's
+HIP kernels.  There is no fallback: if libfdl.so has not been built, importing
+this module raises.  Tensors are torch tensors used as plain device buffers
+(`data_ptr()`); raw integer addresses are accepted too, which is what the
+host-only tests of the argument checks use.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Union
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libfdl.so")
+
+FDL_F32, FDL_BF16 = 0, 1
+FDL_OK, FDL_ERR_NULL, FDL_ERR_SHAPE, FDL_ERR_DTYPE, FDL_ERR_EPS, FDL_ERR_WORKSPACE, FDL_ERR_ALIGN, FDL_ERR_LAUNCH = range(8)
+
+EXPORTS = ("fdl_status_string", "fdl_workspace_bytes", "fdl_forward", "fdl_backward")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_14279_amd.build` "
+                      "(there is no fallback path)")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_vp, _i64, _sz, _f32, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float, ctypes.c_int
+
+_lib.fdl_status_string.restype = ctypes.c_char_p
+_lib.fdl_status_string.argtypes = [_int]
+_lib.fdl_workspace_bytes.restype = _sz
+_lib.fdl_workspace_bytes.argtypes = [_int, _i64, _i64, _i64]
+_lib.fdl_forward.restype = _int
+_lib.fdl_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.fdl_backward.restype = _int
+_lib.fdl_backward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+
+
+class FdlError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(fdl_status_string(status))
+
+
+def _dtype_code(dtype: Union[int, str]) -> int:
+    if isinstance(dtype, str):
+        return {"f32": FDL_F32, "bf16": FDL_BF16}[dtype]
+    return int(dtype)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t or None
+    return t.data_ptr() or None
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def fdl_status_string(status: int) -> str:
+    return _lib.fdl_status_string(int(status)).decode()
+
+
+def fdl_workspace_bytes(dtype, M: int, K: int, N: int) -> int:
+    return int(_lib.fdl_workspace_bytes(_dtype_code(dtype), M, K, N))
+
+
+def fdl_forward_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd,
+                    workspace, workspace_bytes, stream) -> int:
+    """Direct call, returns the status code (no exception)."""
+    return int(_lib.fdl_forward(_dtype_code(dtype), M, K, N, _ptr(X), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                                float(eps), _ptr(Y), _ptr(Zsave), _ptr(mean), _ptr(rstd), _ptr(workspace),
+                                int(workspace_bytes), stream))
+
+
+def fdl_backward_raw(dtype, M, K, N, dY, X, W, gamma, Zsave, mean, rstd, dX, dW, db, dgamma, dbeta,
+                     workspace, workspace_bytes, stream) -> int:
+    return int(_lib.fdl_backward(_dtype_code(dtype), M, K, N, _ptr(dY), _ptr(X), _ptr(W), _ptr(gamma), _ptr(Zsave),
+                                 _ptr(mean), _ptr(rstd), _ptr(dX), _ptr(dW), _ptr(db), _ptr(dgamma), _ptr(dbeta),
+                                 _ptr(workspace), int(workspace_bytes), stream))
+
+
+def fdl_forward(dtype, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, workspace, stream=None) -> None:
+    """Enqueue the forward pass on `stream` (default: torch's current stream).  Shapes come from X [M,K], W [N,K]."""
+    M, K = X.shape
+    N = W.shape[0]
+    st = fdl_forward_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd,
+                         workspace, _nbytes(workspace), _stream(stream))
+    if st != FDL_OK:
+        raise FdlError(st)
+
+
+def fdl_backward(dtype, dY, X, W, gamma, Zsave, mean, rstd, dX, dW, db, dgamma, dbeta, workspace, stream=None) -> None:
+    """Enqueue the backward pass on `stream` (default: torch's current stream)."""
+    M, K = X.shape
+    N = W.shape[0]
+    st = fdl_backward_raw(dtype, M, K, N, dY, X, W, gamma, Zsave, mean, rstd, dX, dW, db, dgamma, dbeta,
+                          workspace, _nbytes(workspace), _stream(stream))
+    if st != FDL_OK:
+        raise FdlError(st)

@@ -1,0 +1,123 @@
+// Shared device-side helpers for the fused dense-layer kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fdl {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) double f64x4;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+
+constexpr int kWave = 64;
+
+// Storage type -> arithmetic type: one level above the storage precision.
+template <class T> struct ComputeOf;
+template <> struct ComputeOf<float> { typedef double type; };
+template <> struct ComputeOf<bf16_t> { typedef float type; };
+
+template <class T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return (float)v; }
+
+// Round a value of the arithmetic type to the storage type (nearest, ties to even).
+template <class T, class C> __device__ __forceinline__ T to_storage(C v);
+template <> __device__ __forceinline__ float to_storage<float, double>(double v) { return (float)v; }
+template <> __device__ __forceinline__ float to_storage<float, float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t to_storage<bf16_t, float>(float v) { return (bf16_t)v; }
+template <> __device__ __forceinline__ bf16_t to_storage<bf16_t, double>(double v) { return (bf16_t)(float)v; }
+
+// ---------------------------------------------------------------------------------------------
+// Standard normal CDF Phi and density phi, the two pieces of GELU_erf and its derivative:
+//   GELU(z) = z Phi(z),   GELU'(z) = Phi(z) + z phi(z).
+// double: library erfc/exp (erfc form keeps relative accuracy for z << 0).
+// float : Phi through the rational-times-exponential erfc approximation of Abramowitz & Stegun
+//         7.1.26 (absolute error <= 1.5e-7 on erf), which shares its exponential exp(-z^2/2) with
+//         phi, so one hardware exp2 and one hardware reciprocal serve both.  Far below what bf16
+//         storage resolves.
+template <class C> struct Gauss;
+
+template <> struct Gauss<double> {
+  static __device__ __forceinline__ void eval(double z, double& Phi, double& phi) {
+    Phi = 0.5 * erfc(-z * 0.70710678118654752440);
+    phi = exp(-0.5 * z * z) * 0.39894228040143267794;
+  }
+  static __device__ __forceinline__ double cdf(double z) { return 0.5 * erfc(-z * 0.70710678118654752440); }
+};
+
+template <> struct Gauss<float> {
+  static __device__ __forceinline__ float tail(float z, float& e) {
+    // returns Phi(-|z|) = 0.5 erfc(|z|/sqrt 2); e = exp(-z^2/2)
+    const float az = __builtin_fabsf(z);
+    e = __builtin_amdgcn_exp2f(-0.72134752044448170368f * z * z);          // exp(-z^2/2)
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f * 0.70710678118654752440f, az, 1.0f));
+    float p = 1.061405429f;
+    p = __builtin_fmaf(p, t, -1.453152027f);
+    p = __builtin_fmaf(p, t, 1.421413741f);
+    p = __builtin_fmaf(p, t, -0.284496736f);
+    p = __builtin_fmaf(p, t, 0.254829592f);
+    return 0.5f * p * t * e;
+  }
+  static __device__ __forceinline__ void eval(float z, float& Phi, float& phi) {
+    float e;
+    const float q = tail(z, e);
+    Phi = z >= 0.0f ? 1.0f - q : q;
+    phi = e * 0.39894228040143267794f;
+  }
+  static __device__ __forceinline__ float cdf(float z) {
+    float e;
+    const float q = tail(z, e);
+    return z >= 0.0f ? 1.0f - q : q;
+  }
+};
+
+template <class C> __device__ __forceinline__ C gelu(C z) { return z * Gauss<C>::cdf(z); }
+
+// ---------------------------------------------------------------------------------------------
+// Vector access helpers: V consecutive storage elements <-> V values of the arithmetic type.
+template <class T, int V> struct VecIO;
+
+template <> struct VecIO<float, 4> {
+  template <class C> static __device__ __forceinline__ void load(const float* p, C (&v)[4]) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p);
+    v[0] = (C)t[0]; v[1] = (C)t[1]; v[2] = (C)t[2]; v[3] = (C)t[3];
+  }
+  template <class C> static __device__ __forceinline__ void store(float* p, const C (&v)[4]) {
+    f32x4 t; t[0] = (float)v[0]; t[1] = (float)v[1]; t[2] = (float)v[2]; t[3] = (float)v[3];
+    *reinterpret_cast<f32x4*>(p) = t;
+  }
+};
+template <> struct VecIO<float, 1> {
+  template <class C> static __device__ __forceinline__ void load(const float* p, C (&v)[1]) { v[0] = (C)p[0]; }
+  template <class C> static __device__ __forceinline__ void store(float* p, const C (&v)[1]) { p[0] = (float)v[0]; }
+};
+template <> struct VecIO<bf16_t, 8> {
+  template <class C> static __device__ __forceinline__ void load(const bf16_t* p, C (&v)[8]) {
+    const bf16x8 t = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (C)(float)t[i];
+  }
+  template <class C> static __device__ __forceinline__ void store(bf16_t* p, const C (&v)[8]) {
+    bf16x8 t;
+#pragma unroll
+    for (int i = 0; i < 8; i++) t[i] = (bf16_t)(float)v[i];
+    *reinterpret_cast<bf16x8*>(p) = t;
+  }
+};
+template <> struct VecIO<bf16_t, 1> {
+  template <class C> static __device__ __forceinline__ void load(const bf16_t* p, C (&v)[1]) { v[0] = (C)(float)p[0]; }
+  template <class C> static __device__ __forceinline__ void store(bf16_t* p, const C (&v)[1]) { p[0] = (bf16_t)(float)v[0]; }
+};
+
+// Sum over the 64 lanes of a wavefront; every lane receives the total.
+template <class C> __device__ __forceinline__ C wave_sum(C v) {
+#pragma unroll
+  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+  return v;
+}
+
+}  // namespace fdl

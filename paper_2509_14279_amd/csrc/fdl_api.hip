@@ -1,0 +1,202 @@
+// C-ABI entry points of libfdl: argument validation, launch plan / workspace layout, and the sequence of
+// kernel launches for the forward and backward pass of the fused dense-layer block.
+#include "../../include/fdl.h"
+#include "internal.h"
+
+#include <cmath>
+
+namespace fdl {
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 24;       // per dimension
+constexpr int64_t kMaxElems = (int64_t)1 << 40;     // per matrix
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+__global__ void zero_f32_kernel(float* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0.0f;
+}
+__global__ void zero_u16_kernel(unsigned short* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+bool shape_ok(int64_t M, int64_t K, int64_t N) {
+  if (M < 0 || K < 1 || N < 1) return false;
+  if (M > kMaxDim || K > kMaxDim || N > kMaxDim) return false;
+  if (M * N > kMaxElems || M * K > kMaxElems || N * K > kMaxElems) return false;
+  return true;
+}
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+}  // namespace
+
+bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
+  if (dt != kF32 && dt != kBF16) return false;
+  if (!shape_ok(M, K, N)) return false;
+  const size_t ts = dt == kF32 ? 4 : 2;   // storage element
+  const size_t cs = dt == kF32 ? 8 : 4;   // arithmetic element
+  Plan q = {};
+  q.dt = dt; q.M = M; q.K = K; q.N = N;
+  const int64_t Mp = M > 0 ? M : 1;
+
+  // ---- forward
+  q.f1_fast = dt == kBF16 && fast_f1_supported(M, K, N);
+  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  q.f1_wb = pick_wb(Mp, N);
+  q.stat_tile_w = q.f1_fast ? fast_f1_stat_tile_w() : 16 * q.f1_wb;
+  q.stat_tiles = (int)((N + q.stat_tile_w - 1) / q.stat_tile_w);
+  size_t off = 0;
+  q.off_part = off; off += align256((size_t)q.stat_tiles * Mp * 8);
+  q.fwd_bytes = off;
+
+  // ---- backward
+  q.b1_fused = b1_fused_supported(dt, N);
+  if (q.b1_fused) {
+    q.b1_groups = (int)(Mp < 512 ? Mp : 512);
+    q.b1_rows_per_group = 0;
+  } else {
+    int64_t rpg = (Mp + 1023) / 1024;
+    if (rpg < 16) rpg = 16;
+    q.b1_rows_per_group = (int)rpg;
+    q.b1_groups = (int)((Mp + rpg - 1) / rpg);
+  }
+  q.b3_fast = dt == kBF16 && fast_b3_supported(M, K, N);
+  q.b4_fast = dt == kBF16 && fast_b4_supported(M, K, N);
+  q.b3_wb = pick_wb(Mp, K);
+  q.b4_wb = pick_wb(N, K);
+  q.b4_split = q.b4_fast ? fast_b4_split(M, K, N) : 1;
+  off = 0;
+  q.off_dz = off; off += align256((size_t)Mp * N * ts);
+  q.off_c12 = off; off += align256(q.b1_fused ? 0 : (size_t)2 * Mp * cs);
+  q.off_colpart = off; off += align256((size_t)q.b1_groups * 3 * N * cs);
+  q.off_wt = off; off += align256(q.b3_fast ? (size_t)K * N * ts : 0);
+  q.off_dwpart = off; off += align256(q.b4_split > 1 ? (size_t)q.b4_split * N * K * 4 : 0);
+  q.bwd_bytes = off;
+  q.bytes = q.fwd_bytes > q.bwd_bytes ? q.fwd_bytes : q.bwd_bytes;
+  *p = q;
+  return true;
+}
+
+}  // namespace fdl
+
+using namespace fdl;
+
+extern "C" const char* fdl_status_string(fdl_status s) {
+  switch (s) {
+    case FDL_OK: return "FDL_OK";
+    case FDL_ERR_NULL: return "FDL_ERR_NULL: a required pointer is NULL";
+    case FDL_ERR_SHAPE: return "FDL_ERR_SHAPE: M, K or N out of the supported range";
+    case FDL_ERR_DTYPE: return "FDL_ERR_DTYPE: unknown dtype";
+    case FDL_ERR_EPS: return "FDL_ERR_EPS: eps must be finite and >= 0";
+    case FDL_ERR_WORKSPACE: return "FDL_ERR_WORKSPACE: workspace missing or too small";
+    case FDL_ERR_ALIGN: return "FDL_ERR_ALIGN: pointer not sufficiently aligned";
+    case FDL_ERR_LAUNCH: return "FDL_ERR_LAUNCH: HIP reported a launch error";
+  }
+  return "unknown fdl_status";
+}
+
+extern "C" size_t fdl_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N) {
+  Plan p;
+  if (!make_plan((int)dt, M, K, N, &p)) return 0;
+  return p.bytes;
+}
+
+static fdl_status check_common(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* workspace,
+                               size_t workspace_bytes, Plan* p) {
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  if (!make_plan((int)dt, M, K, N, p)) return FDL_ERR_SHAPE;
+  if (workspace == nullptr || workspace_bytes < p->bytes) return FDL_ERR_WORKSPACE;
+  if (!aligned(workspace, 256)) return FDL_ERR_ALIGN;
+  return FDL_OK;
+}
+
+static fdl_status launch_status() { return hipGetLastError() == hipSuccess ? FDL_OK : FDL_ERR_LAUNCH; }
+
+extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
+                                  const float* b, const float* gamma, const float* beta, float eps, void* Y,
+                                  void* Zsave, float* mean, float* rstd, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  if (!X || !W || !b || !gamma || !beta || !Y || !Zsave || !mean || !rstd) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return FDL_ERR_EPS;
+  Plan p;
+  const fdl_status st = check_common(dt, M, K, N, workspace, workspace_bytes, &p);
+  if (st != FDL_OK) return st;
+  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(Zsave, 16) || !aligned(b, 4) ||
+      !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) || !aligned(rstd, 4))
+    return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  void* part = ws + p.off_part;
+
+  // F1
+  if (p.f1_fast) {
+    launch_fast_f1(M, K, N, X, W, b, Zsave, part, s);
+  } else {
+    GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
+    launch_generic_f1((int)dt, g, b, Zsave, part, s);
+  }
+  // FS, F2
+  launch_stats_finalize(part, p.stat_tiles, p.stat_tile_w, M, N, eps, mean, rstd, s);
+  launch_f2((int)dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+  return launch_status();
+}
+
+extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* dY, const void* X,
+                                   const void* W, const float* gamma, const void* Zsave, const float* mean,
+                                   const float* rstd, void* dX, void* dW, float* db, float* dgamma, float* dbeta,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!dY || !X || !W || !gamma || !Zsave || !mean || !rstd || !dX || !dW || !db || !dgamma || !dbeta)
+    return FDL_ERR_NULL;
+  Plan p;
+  const fdl_status st = check_common(dt, M, K, N, workspace, workspace_bytes, &p);
+  if (st != FDL_OK) return st;
+  if (!aligned(dY, 16) || !aligned(X, 16) || !aligned(W, 16) || !aligned(Zsave, 16) || !aligned(dX, 16) ||
+      !aligned(dW, 16) || !aligned(gamma, 4) || !aligned(mean, 4) || !aligned(rstd, 4) || !aligned(db, 4) ||
+      !aligned(dgamma, 4) || !aligned(dbeta, 4))
+    return FDL_ERR_ALIGN;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (M == 0) {
+    // no rows: every sum over rows is empty
+    const int64_t nk = N * K;
+    if (dt == FDL_F32) hipLaunchKernelGGL(zero_f32_kernel, dim3(256), dim3(256), 0, s, (float*)dW, nk);
+    else hipLaunchKernelGGL(zero_u16_kernel, dim3(256), dim3(256), 0, s, (unsigned short*)dW, nk);
+    hipLaunchKernelGGL(zero_f32_kernel, dim3(8), dim3(256), 0, s, db, N);
+    hipLaunchKernelGGL(zero_f32_kernel, dim3(8), dim3(256), 0, s, dgamma, N);
+    hipLaunchKernelGGL(zero_f32_kernel, dim3(8), dim3(256), 0, s, dbeta, N);
+    return launch_status();
+  }
+  char* ws = static_cast<char*>(workspace);
+  void* dZ = ws + p.off_dz;
+  void* c12 = ws + p.off_c12;
+  void* colpart = ws + p.off_colpart;
+
+  // B1, B2
+  if (p.b1_fused) {
+    launch_b1_fused((int)dt, M, N, p.b1_groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  } else {
+    launch_b1a((int)dt, M, N, dY, Zsave, gamma, mean, rstd, c12, s);
+    launch_b1b((int)dt, M, N, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+  }
+  launch_b2((int)dt, N, p.b1_groups, colpart, dbeta, dgamma, db, s);
+
+  // B3: dX[M,K] = dZ[M,N] W[N,K]
+  if (p.b3_fast) {
+    void* Wt = ws + p.off_wt;
+    launch_transpose_bf16(N, K, W, Wt, s);
+    launch_fast_b3(M, K, N, dZ, Wt, dX, s);
+  } else {
+    GemmDesc g = {dZ, W, M, K, N, N, K, true, false, p.b3_wb};
+    launch_generic_store((int)dt, g, dX, s);
+  }
+  // B4: dW[N,K] = dZ^T[N,M] X[M,K]
+  if (p.b4_fast) {
+    launch_fast_b4(M, K, N, p.b4_split, dZ, X, dW, ws + p.off_dwpart, s);
+  } else {
+    GemmDesc g = {dZ, X, N, K, M, N, K, false, false, p.b4_wb};
+    launch_generic_store((int)dt, g, dW, s);
+  }
+  return launch_status();
+}

@@ -1,0 +1,293 @@
+// Generic MFMA GEMM for the fused dense-layer block: any shape, any alignment, both storage types.
+//
+//     C[i][j] = sum_r A(i,r) * B(j,r)          I x J outputs, reduction length R
+//
+// Used for all three contractions of the block when the tuned bf16 kernel does not apply:
+//   F1  Z  = X W^T + b   A = X  (r = k contiguous)   B = W  (r = k contiguous)
+//   B3  dX = dZ W        A = dZ (r = n contiguous)   B = W  (r = n is the row index)
+//   B4  dW = dZ^T X      A = dZ (r = m is the row index)   B = X (r = m is the row index)
+// (the three linear-layer products of the paper's linear forward/backward tasks, appendix
+// "Highlighted CUDA Kernels: Code", done here on the matrix cores instead of one thread or warp per
+// output element).
+//
+// Storage fp32  -> operands widened to fp64 in registers, v_mfma_f64_16x16x4_f64, fp64 accumulators.
+// Storage bf16  -> operands widened to fp32 at the global load, v_mfma_f32_16x16x4_f32, fp32 accumulators.
+// Both instructions take one A and one B value per lane (row/col = lane%16, k = lane/16); the kernel
+// assigns reduction index 4*(lane/16)+s to MFMA step s of a 16-deep slice for A and B alike, which lets an
+// r-contiguous operand be read from LDS with one 16-byte read per four MFMA steps.
+//
+// Workgroup: 256 threads = 4 waves as 2x2; wave tile (16*WB)^2; block tile (32*WB)^2; 16-deep reduction
+// slices, double-buffered in LDS with the next slice's global loads in flight during the MFMAs.
+#include "common.hip.h"
+#include "internal.h"
+
+namespace fdl {
+namespace {
+
+enum { EPI_STORE = 0, EPI_F1 = 1 };
+
+struct GemmParams {
+  const void* A; const void* B; void* C;
+  const float* bias; f32x2* part;
+  int64_t I, J, R, lda, ldb;
+  int a_vec, b_vec;
+};
+
+template <class AccT> struct Mma;
+template <> struct Mma<double> {
+  typedef f64x4 acc_t;
+  static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64((double)a, (double)b, c, 0, 0, 0);
+  }
+  // accumulator register r of lane l holds output row 4r + l/16, column l%16
+  static __device__ __forceinline__ int row(int lane, int r) { return r * 4 + (lane >> 4); }
+};
+template <> struct Mma<float> {
+  typedef f32x4 acc_t;
+  static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+  }
+  // accumulator register r of lane l holds output row 4(l/16) + r, column l%16
+  static __device__ __forceinline__ int row(int lane, int r) { return (lane >> 4) * 4 + r; }
+};
+
+template <class T> __device__ __forceinline__ void load4(const T* p, float (&v)[4]);
+template <> __device__ __forceinline__ void load4<float>(const float* p, float (&v)[4]) {
+  const f32x4 t = *reinterpret_cast<const f32x4*>(p);
+  v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float (&v)[4]) {
+  const bf16x4 t = *reinterpret_cast<const bf16x4*>(p);
+  v[0] = (float)t[0]; v[1] = (float)t[1]; v[2] = (float)t[2]; v[3] = (float)t[3];
+}
+
+// One operand's BT x 16 slice: global -> registers -> LDS, and LDS -> MFMA fragments.
+// RC  (reduction-contiguous in memory): LDS layout [BT][20] floats (16 + 4 pad: 16-byte accesses of 8
+//      consecutive rows fall on 8 disjoint groups of 4 banks).
+// !RC (row index is the reduction index): LDS layout [16][BT+4] floats.
+template <class T, bool RC, int BT> struct Operand {
+  static constexpr int kChunks = BT * 16 / 4;
+  static constexpr int kPerThread = kChunks / 256;
+  static constexpr int kFloats = BT * 20;
+  static_assert(kPerThread >= 1, "block tile too small for 256 threads");
+
+  static __device__ __forceinline__ void fetch(const T* base, int64_t ld, int64_t i0, int64_t I, int64_t r0, int64_t R,
+                                               bool vec_ok, int tid, float (&reg)[kPerThread][4]) {
+#pragma unroll
+    for (int q = 0; q < kPerThread; q++) {
+      const int c = tid + q * 256;
+      if (RC) {
+        const int64_t gi = i0 + (c >> 2), gr = r0 + (c & 3) * 4;
+        const T* ptr = base + gi * ld + gr;
+        if (vec_ok && gi < I && gr + 3 < R) {
+          load4<T>(ptr, reg[q]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; e++) reg[q][e] = (gi < I && gr + e < R) ? to_f32<T>(ptr[e]) : 0.0f;
+        }
+      } else {
+        const int64_t gr = r0 + c / (BT / 4), gi = i0 + (c % (BT / 4)) * 4;
+        const T* ptr = base + gr * ld + gi;
+        if (vec_ok && gr < R && gi + 3 < I) {
+          load4<T>(ptr, reg[q]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; e++) reg[q][e] = (gr < R && gi + e < I) ? to_f32<T>(ptr[e]) : 0.0f;
+        }
+      }
+    }
+  }
+
+  static __device__ __forceinline__ void stash(float* lds, int tid, const float (&reg)[kPerThread][4]) {
+#pragma unroll
+    for (int q = 0; q < kPerThread; q++) {
+      const int c = tid + q * 256;
+      f32x4 t; t[0] = reg[q][0]; t[1] = reg[q][1]; t[2] = reg[q][2]; t[3] = reg[q][3];
+      if (RC) {
+        *reinterpret_cast<f32x4*>(lds + (c >> 2) * 20 + (c & 3) * 4) = t;
+      } else {
+        *reinterpret_cast<f32x4*>(lds + (c / (BT / 4)) * (BT + 4) + (c % (BT / 4)) * 4) = t;
+      }
+    }
+  }
+
+  // fragment for tile row `row` (within the block tile): the 4 reduction indices 4g..4g+3, g = lane/16
+  static __device__ __forceinline__ void frag(const float* lds, int row, int g, float (&f)[4]) {
+    if (RC) {
+      const f32x4 t = *reinterpret_cast<const f32x4*>(lds + row * 20 + g * 4);
+      f[0] = t[0]; f[1] = t[1]; f[2] = t[2]; f[3] = t[3];
+    } else {
+#pragma unroll
+      for (int s = 0; s < 4; s++) f[s] = lds[(g * 4 + s) * (BT + 4) + row];
+    }
+  }
+};
+
+template <class T, class AccT, bool A_RC, bool B_RC, int WB, int EPI>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
+  constexpr int BT = 32 * WB;
+  typedef Operand<T, A_RC, BT> OpA;
+  typedef Operand<T, B_RC, BT> OpB;
+  typedef typename Mma<AccT>::acc_t acc_t;
+  __shared__ __attribute__((aligned(16))) float lds[2][2][BT * 20];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wi = wave >> 1, wj = wave & 1;
+  const int64_t tiles_j = (p.J + BT - 1) / BT;
+  const int64_t i0 = (int64_t)(blockIdx.x / tiles_j) * BT, j0 = (int64_t)(blockIdx.x % tiles_j) * BT;
+  const T* A = static_cast<const T*>(p.A);
+  const T* B = static_cast<const T*>(p.B);
+
+  acc_t acc[WB][WB];
+#pragma unroll
+  for (int a = 0; a < WB; a++)
+#pragma unroll
+    for (int b = 0; b < WB; b++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) acc[a][b][r] = 0;
+
+  float ra[OpA::kPerThread][4], rb[OpB::kPerThread][4];
+  const int64_t slices = (p.R + 15) / 16;
+  OpA::fetch(A, p.lda, i0, p.I, 0, p.R, p.a_vec != 0, tid, ra);
+  OpB::fetch(B, p.ldb, j0, p.J, 0, p.R, p.b_vec != 0, tid, rb);
+  OpA::stash(lds[0][0], tid, ra);
+  OpB::stash(lds[0][1], tid, rb);
+  __syncthreads();
+
+  const int g = lane >> 4, l16 = lane & 15;
+  for (int64_t kt = 0; kt < slices; kt++) {
+    const int cur = (int)(kt & 1);
+    const bool more = kt + 1 < slices;
+    if (more) {
+      OpA::fetch(A, p.lda, i0, p.I, (kt + 1) * 16, p.R, p.a_vec != 0, tid, ra);
+      OpB::fetch(B, p.ldb, j0, p.J, (kt + 1) * 16, p.R, p.b_vec != 0, tid, rb);
+    }
+    float fa[WB][4], fb[WB][4];
+#pragma unroll
+    for (int a = 0; a < WB; a++) OpA::frag(lds[cur][0], wi * 16 * WB + a * 16 + l16, g, fa[a]);
+#pragma unroll
+    for (int b = 0; b < WB; b++) OpB::frag(lds[cur][1], wj * 16 * WB + b * 16 + l16, g, fb[b]);
+#pragma unroll
+    for (int s = 0; s < 4; s++)
+#pragma unroll
+      for (int a = 0; a < WB; a++)
+#pragma unroll
+        for (int b = 0; b < WB; b++) acc[a][b] = Mma<AccT>::mma(fa[a][s], fb[b][s], acc[a][b]);
+    if (more) {
+      OpA::stash(lds[cur ^ 1][0], tid, ra);
+      OpB::stash(lds[cur ^ 1][1], tid, rb);
+    }
+    __syncthreads();
+  }
+
+  // ------------------------------------------------------------------ epilogue
+  const int64_t iw = i0 + wi * 16 * WB, jw = j0 + wj * 16 * WB;
+  T* C = static_cast<T*>(p.C);
+  if (EPI == EPI_STORE) {
+#pragma unroll
+    for (int a = 0; a < WB; a++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int64_t i = iw + a * 16 + Mma<AccT>::row(lane, r);
+#pragma unroll
+        for (int b = 0; b < WB; b++) {
+          const int64_t j = jw + b * 16 + l16;
+          if (i < p.I && j < p.J) C[i * p.J + j] = to_storage<T, AccT>(acc[a][b][r]);
+        }
+      }
+  } else {
+    // Z = acc + bias, stored rounded; A = GELU(stored Z); two-pass mean / sum of squared deviations over
+    // this wave's 16*WB columns of the row, reduced across the 16 lanes that share the row.
+    const int64_t tile = jw / (16 * WB);
+    int64_t nvalid = p.J - jw;
+    if (nvalid > 16 * WB) nvalid = 16 * WB;
+    float bias[WB];
+#pragma unroll
+    for (int b = 0; b < WB; b++) { const int64_t j = jw + b * 16 + l16; bias[b] = j < p.J ? p.bias[j] : 0.0f; }
+#pragma unroll
+    for (int a = 0; a < WB; a++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int64_t i = iw + a * 16 + Mma<AccT>::row(lane, r);
+        AccT act[WB];
+        AccT sum = 0;
+#pragma unroll
+        for (int b = 0; b < WB; b++) {
+          const int64_t j = jw + b * 16 + l16;
+          const T zs = to_storage<T, AccT>(acc[a][b][r] + (AccT)bias[b]);
+          const bool ok = j < p.J;
+          if (ok && i < p.I) C[i * p.J + j] = zs;
+          act[b] = ok ? gelu<AccT>((AccT)to_f32<T>(zs)) : (AccT)0;
+          sum += act[b];
+        }
+#pragma unroll
+        for (int m = 1; m <= 8; m <<= 1) sum += __shfl_xor(sum, m, kWave);
+        const AccT mean = nvalid > 0 ? sum / (AccT)nvalid : (AccT)0;
+        AccT m2 = 0;
+#pragma unroll
+        for (int b = 0; b < WB; b++) {
+          const int64_t j = jw + b * 16 + l16;
+          const AccT d = act[b] - mean;
+          m2 += j < p.J ? d * d : (AccT)0;
+        }
+#pragma unroll
+        for (int m = 1; m <= 8; m <<= 1) m2 += __shfl_xor(m2, m, kWave);
+        if (l16 == 0 && i < p.I && nvalid > 0) {
+          f32x2 o; o[0] = (float)mean; o[1] = (float)m2;
+          p.part[tile * p.I + i] = o;
+        }
+      }
+  }
+}
+
+template <class T, bool A_RC, bool B_RC, int WB, int EPI>
+void launch_one(const GemmParams& p, hipStream_t s) {
+  typedef typename ComputeOf<T>::type AccT;
+  constexpr int BT = 32 * WB;
+  const int64_t tiles = ((p.I + BT - 1) / BT) * ((p.J + BT - 1) / BT);
+  hipLaunchKernelGGL((gemm_generic_kernel<T, AccT, A_RC, B_RC, WB, EPI>), dim3((unsigned)tiles), dim3(256), 0, s, p);
+}
+
+template <class T, int EPI> void dispatch(const GemmDesc& g, GemmParams p, hipStream_t s) {
+  // vector loads need an aligned base and a leading dimension that keeps every 4-element chunk aligned
+  const size_t chunk_bytes = 4 * sizeof(T);
+  p.a_vec = ((uintptr_t)g.A % chunk_bytes == 0) && (g.lda % 4 == 0);
+  p.b_vec = ((uintptr_t)g.B % chunk_bytes == 0) && (g.ldb % 4 == 0);
+  const bool big = g.wb == 4;
+  if (EPI == EPI_F1) {           // F1 always has both operands reduction-contiguous
+    if (big) launch_one<T, true, true, 4, EPI>(p, s); else launch_one<T, true, true, 2, EPI>(p, s);
+    return;
+  }
+  if (g.a_rc && !g.b_rc) {
+    if (big) launch_one<T, true, false, 4, EPI>(p, s); else launch_one<T, true, false, 2, EPI>(p, s);
+  } else if (!g.a_rc && !g.b_rc) {
+    if (big) launch_one<T, false, false, 4, EPI>(p, s); else launch_one<T, false, false, 2, EPI>(p, s);
+  } else if (g.a_rc && g.b_rc) {
+    if (big) launch_one<T, true, true, 4, EPI>(p, s); else launch_one<T, true, true, 2, EPI>(p, s);
+  } else {
+    if (big) launch_one<T, false, true, 4, EPI>(p, s); else launch_one<T, false, true, 2, EPI>(p, s);
+  }
+}
+
+GemmParams base_params(const GemmDesc& g) {
+  GemmParams p;
+  p.A = g.A; p.B = g.B; p.C = nullptr; p.bias = nullptr; p.part = nullptr;
+  p.I = g.I; p.J = g.J; p.R = g.R; p.lda = g.lda; p.ldb = g.ldb; p.a_vec = 0; p.b_vec = 0;
+  return p;
+}
+
+}  // namespace
+
+void launch_generic_f1(int dt, const GemmDesc& g, const float* bias, void* Zsave, void* part, hipStream_t s) {
+  GemmParams p = base_params(g);
+  p.C = Zsave; p.bias = bias; p.part = static_cast<f32x2*>(part);
+  if (dt == kF32) dispatch<float, EPI_F1>(g, p, s); else dispatch<bf16_t, EPI_F1>(g, p, s);
+}
+
+void launch_generic_store(int dt, const GemmDesc& g, void* C, hipStream_t s) {
+  GemmParams p = base_params(g);
+  p.C = C;
+  if (dt == kF32) dispatch<float, EPI_STORE>(g, p, s); else dispatch<bf16_t, EPI_STORE>(g, p, s);
+}
+
+}  // namespace fdl

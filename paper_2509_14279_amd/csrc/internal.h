@@ -1,0 +1,94 @@
+// Host-side declarations shared by the translation units of libfdl: the launch plan (which
+// kernels run, how the workspace is carved up) and one launcher per phase of the block.
+//
+// Phases:  F1  Z = X W^T + b, Zsave, per-(row, column tile) partial statistics of GELU(Zsave)
+//          FS  merge partial statistics -> mean, rstd
+//          F2  Y = (GELU(Zsave) - mean) rstd gamma + beta
+//          B1  dZ and the column partials of dbeta, dgamma, db  (B1a: row sums c1, c2 first)
+//          B2  column partials -> dbeta, dgamma, db
+//          B3  dX = dZ W            B4  dW = dZ^T X
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace fdl {
+
+enum DType { kF32 = 0, kBF16 = 1 };
+
+struct Plan {
+  int dt;
+  int64_t M, K, N;
+  // forward
+  int f1_fast;            // 1: bf16 fast MFMA kernel, 0: generic kernel
+  int f1_wb;              // generic kernel: 16x16 blocks per wave tile side (wave tile = 16*wb)
+  int stat_tile_w;        // width of one partial-statistics column tile
+  int stat_tiles;         // number of such tiles per row
+  size_t off_part;        // float2 [stat_tiles][M]
+  size_t fwd_bytes;
+  // backward
+  int b1_fused;           // 1: one pass with the row held in registers; 0: B1a + B1b
+  int b1_groups;          // number of row groups that produce column partials
+  int b1_rows_per_group;  // B1b only
+  int b3_fast, b4_fast;
+  int b3_wb, b4_wb;
+  int b4_split;           // split of the reduction over M in B4 (fast kernel)
+  size_t off_dz;          // T [M][N]
+  size_t off_c12;         // C [2][M]
+  size_t off_colpart;     // C [groups][3][N]
+  size_t off_wt;          // T [K][N]   (W transposed, fast B3)
+  size_t off_dwpart;      // float [split][N][K]
+  size_t bwd_bytes;
+  size_t bytes;           // max(fwd, bwd)
+};
+
+// Returns false when the shape or dtype is not supported.
+bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p);
+
+// ---- generic MFMA GEMM: C[i][j] = sum_r A(i,r) B(j,r), any shape, any alignment -----------------
+// a_rc / b_rc: the operand is contiguous along the reduction index r (element (i,r) at A[i*ld + r]);
+// otherwise it is contiguous along i (element (i,r) at A[r*ld + i]).
+struct GemmDesc {
+  const void* A; const void* B;
+  int64_t I, J, R;
+  int64_t lda, ldb;
+  bool a_rc, b_rc;
+  int wb;
+};
+// F1: C = Zsave [I][J] (storage type), bias [J], partial statistics part[tile][I] (float2).
+void launch_generic_f1(int dt, const GemmDesc& g, const float* bias, void* Zsave, void* part, hipStream_t s);
+// plain store: C [I][J] in the storage type
+void launch_generic_store(int dt, const GemmDesc& g, void* C, hipStream_t s);
+
+// ---- row-wise / column-wise phases ------------------------------------------------------------
+void launch_stats_finalize(const void* part, int tiles, int tile_w, int64_t M, int64_t N, float eps,
+                           float* mean, float* rstd, hipStream_t s);
+void launch_f2(int dt, int64_t M, int64_t N, const void* Zsave, const float* mean, const float* rstd,
+               const float* gamma, const float* beta, void* Y, hipStream_t s);
+void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave, const float* gamma,
+                const float* mean, const float* rstd, void* c12, hipStream_t s);
+void launch_b1b(int dt, int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Zsave,
+                const float* gamma, const float* mean, const float* rstd, const void* c12, void* dZ,
+                void* colpart, hipStream_t s);
+// fused single pass (row held in registers); returns false if this N is not supported by it
+bool b1_fused_supported(int dt, int64_t N);
+void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, const void* dY, const void* Zsave,
+                     const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart,
+                     hipStream_t s);
+void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
+               hipStream_t s);
+
+// ---- bf16 fast path -----------------------------------------------------------------------------
+bool fast_f1_supported(int64_t M, int64_t K, int64_t N);
+bool fast_b3_supported(int64_t M, int64_t K, int64_t N);
+bool fast_b4_supported(int64_t M, int64_t K, int64_t N);
+int fast_f1_stat_tile_w();
+void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
+                    void* part, hipStream_t s);
+void launch_transpose_bf16(int64_t rows, int64_t cols, const void* in, void* out, hipStream_t s);
+void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* Wt, void* dX, hipStream_t s);
+int fast_b4_split(int64_t M, int64_t K, int64_t N);
+void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dW,
+                    void* dwpart, hipStream_t s);
+
+}  // namespace fdl

@@ -1,0 +1,426 @@
+// Streaming (HBM-bound) phases of the fused dense-layer block: LayerNorm statistics merge and
+// normalisation (forward), the LayerNorm/GELU gradient row pass with its column partial sums
+// (backward), and the column reduction that finishes dbeta, dgamma, db.
+//
+// Row reductions follow the idiom of the paper's row-normalisation kernels (appendix "Highlighted CUDA
+// Kernels", LayerNorm forward and Llama RMSNorm forward: vector loads, wavefront shuffles, a small LDS
+// exchange between wavefronts) with 64-wide wavefronts; the bias-style column sums are laid out so that
+// consecutive lanes read consecutive columns (the paper's linear backward bias kernel walks a column with
+// stride N instead).
+//
+// Arithmetic type C is one level above the storage type T: fp64 for fp32 storage, fp32 for bf16 storage.
+#include "common.hip.h"
+#include "internal.h"
+
+namespace fdl {
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// FS: merge per-(row, column tile) partial (mean, sum of squared deviations) pairs with the pairwise
+// update of Chan et al., in fp64; one thread per row.  part is [tiles][M].
+__global__ __launch_bounds__(256) void stats_finalize_kernel(const f32x2* __restrict__ part, int tiles, int tile_w,
+                                                             int64_t M, int64_t N, float eps,
+                                                             float* __restrict__ mean, float* __restrict__ rstd) {
+  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (m >= M) return;
+  double na = 0.0, mu = 0.0, m2 = 0.0;
+  for (int t = 0; t < tiles; t++) {
+    int64_t nb = N - (int64_t)t * tile_w;
+    if (nb <= 0) break;
+    if (nb > tile_w) nb = tile_w;
+    const f32x2 p = part[(int64_t)t * M + m];
+    const double d = (double)p[0] - mu, n = na + (double)nb;
+    mu += d * (double)nb / n;
+    m2 += (double)p[1] + d * d * na * (double)nb / n;
+    na = n;
+  }
+  mean[m] = (float)mu;
+  rstd[m] = (float)(1.0 / sqrt(m2 / (double)N + (double)eps));
+}
+
+// ------------------------------------------------------------------------------------------------
+// F2: Y = (GELU(Zsave) - mean) * rstd * gamma + beta.  A workgroup owns a strip of 256*V columns and a
+// block of rows; gamma and beta for the thread's V columns stay in registers across the rows.
+template <class T, int V>
+__global__ __launch_bounds__(256) void f2_kernel(int64_t M, int64_t N, int rows_per_wg, int strips,
+                                                 const T* __restrict__ Z, const float* __restrict__ mean,
+                                                 const float* __restrict__ rstd, const float* __restrict__ gamma,
+                                                 const float* __restrict__ beta, T* __restrict__ Y) {
+  typedef typename ComputeOf<T>::type C;
+  const int strip = blockIdx.x % strips;
+  const int64_t rb = blockIdx.x / strips;
+  const int64_t col = ((int64_t)strip * 256 + threadIdx.x) * V;
+  if (col >= N) return;
+  C gm[V], bt[V];
+#pragma unroll
+  for (int v = 0; v < V; v++) { gm[v] = (C)gamma[col + v]; bt[v] = (C)beta[col + v]; }
+  const int64_t r0 = rb * rows_per_wg;
+  int64_t r1 = r0 + rows_per_wg;
+  if (r1 > M) r1 = M;
+#pragma unroll 4
+  for (int64_t r = r0; r < r1; r++) {
+    C z[V], y[V];
+    VecIO<T, V>::load(Z + r * N + col, z);
+    const C mu = (C)mean[r], rs = (C)rstd[r];
+#pragma unroll
+    for (int v = 0; v < V; v++) y[v] = (gelu<C>(z[v]) - mu) * rs * gm[v] + bt[v];
+    VecIO<T, V>::store(Y + r * N + col, y);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// sum of two values over a workgroup of NW wavefronts; `red` is this call's LDS slot ([NW][2] of C)
+template <class C, int NW> __device__ __forceinline__ void wg_sum2(C& a, C& b, C (*red)[2]) {
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int wave = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) { red[wave][0] = a; red[wave][1] = b; }
+  __syncthreads();
+  a = red[0][0];
+  b = red[0][1];
+#pragma unroll
+  for (int w = 1; w < NW; w++) { a += red[w][0]; b += red[w][1]; }
+}
+
+// B1a (two-kernel path): c1_i = mean_j g_ij, c2_i = mean_j g_ij Ahat_ij with g = dY gamma.
+template <class T, int V>
+__global__ __launch_bounds__(256) void b1a_kernel(int64_t M, int64_t N, const T* __restrict__ dY,
+                                                  const T* __restrict__ Z, const float* __restrict__ gamma,
+                                                  const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                  typename ComputeOf<T>::type* __restrict__ c12) {
+  typedef typename ComputeOf<T>::type C;
+  __shared__ C red[2][4][2];
+  int par = 0;
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x, par ^= 1) {
+    const C mu = (C)mean[row], rs = (C)rstd[row];
+    C s1 = 0, s2 = 0;
+    for (int64_t col = (int64_t)threadIdx.x * V; col < N; col += 256 * V) {
+      C dy[V], z[V];
+      VecIO<T, V>::load(dY + row * N + col, dy);
+      VecIO<T, V>::load(Z + row * N + col, z);
+#pragma unroll
+      for (int v = 0; v < V; v++) {
+        const C g = dy[v] * (C)gamma[col + v];
+        const C ah = (gelu<C>(z[v]) - mu) * rs;
+        s1 += g;
+        s2 += g * ah;
+      }
+    }
+    wg_sum2<C, 4>(s1, s2, red[par]);
+    if (threadIdx.x == 0) { c12[row] = s1 / (C)N; c12[M + row] = s2 / (C)N; }
+  }
+}
+
+// B1b (two-kernel path): dZ and column partials, given c1 and c2.
+template <class T, int V>
+__global__ __launch_bounds__(256) void b1b_kernel(int64_t M, int64_t N, int rows_per_group, int strips,
+                                                  const T* __restrict__ dY, const T* __restrict__ Z,
+                                                  const float* __restrict__ gamma, const float* __restrict__ mean,
+                                                  const float* __restrict__ rstd,
+                                                  const typename ComputeOf<T>::type* __restrict__ c12,
+                                                  T* __restrict__ dZ, typename ComputeOf<T>::type* __restrict__ colpart) {
+  typedef typename ComputeOf<T>::type C;
+  const int strip = blockIdx.x % strips;
+  const int64_t grp = blockIdx.x / strips;
+  const int64_t col = ((int64_t)strip * 256 + threadIdx.x) * V;
+  if (col >= N) return;
+  C gm[V], accb[V], accg[V], accz[V];
+#pragma unroll
+  for (int v = 0; v < V; v++) { gm[v] = (C)gamma[col + v]; accb[v] = 0; accg[v] = 0; accz[v] = 0; }
+  const int64_t r0 = grp * rows_per_group;
+  int64_t r1 = r0 + rows_per_group;
+  if (r1 > M) r1 = M;
+#pragma unroll 2
+  for (int64_t r = r0; r < r1; r++) {
+    C dy[V], z[V], dz[V];
+    VecIO<T, V>::load(dY + r * N + col, dy);
+    VecIO<T, V>::load(Z + r * N + col, z);
+    const C mu = (C)mean[r], rs = (C)rstd[r], c1 = c12[r], c2 = c12[M + r];
+#pragma unroll
+    for (int v = 0; v < V; v++) {
+      C Phi, phi;
+      Gauss<C>::eval(z[v], Phi, phi);
+      const C ah = (z[v] * Phi - mu) * rs;
+      const C g = dy[v] * gm[v];
+      dz[v] = rs * (g - c1 - ah * c2) * (Phi + z[v] * phi);
+      accb[v] += dy[v];
+      accg[v] += dy[v] * ah;
+      accz[v] += dz[v];
+    }
+    VecIO<T, V>::store(dZ + r * N + col, dz);
+  }
+#pragma unroll
+  for (int v = 0; v < V; v++) {
+    colpart[(grp * 3 + 0) * N + col + v] = accb[v];
+    colpart[(grp * 3 + 1) * N + col + v] = accg[v];
+    colpart[(grp * 3 + 2) * N + col + v] = accz[v];
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// B1 fused: one pass, the row held in registers (S strips of NT*V columns, NT threads).  A workgroup walks rows
+// blockIdx.x, blockIdx.x + gridDim.x, ... ; the next row's loads are issued before the current row's
+// arithmetic; one barrier per row (the LDS exchange slot alternates with the row parity).
+template <class T, int V> struct RawVec;
+template <> struct RawVec<float, 4> { typedef f32x4 type; };
+template <> struct RawVec<float, 1> { typedef float type; };
+template <> struct RawVec<bf16_t, 8> { typedef bf16x8 type; };
+template <> struct RawVec<bf16_t, 1> { typedef bf16_t type; };
+
+template <class T, int V> __device__ __forceinline__ typename RawVec<T, V>::type raw_load(const T* p) {
+  return *reinterpret_cast<const typename RawVec<T, V>::type*>(p);
+}
+template <class T, int V, class C> __device__ __forceinline__ C raw_get(const typename RawVec<T, V>::type& r, int v) {
+  if constexpr (V == 1) return (C)to_f32<T>(r); else return (C)to_f32<T>(r[v]);
+}
+template <class T, int V> __device__ __forceinline__ typename RawVec<T, V>::type raw_zero() {
+  typename RawVec<T, V>::type r;
+  if constexpr (V == 1) r = (T)0.0f; else { for (int v = 0; v < V; v++) r[v] = (T)0.0f; }
+  return r;
+}
+
+template <class T, int V, int S, int NT>
+__global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, const T* __restrict__ dY,
+                                                       const T* __restrict__ Z, const float* __restrict__ gamma,
+                                                       const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                       T* __restrict__ dZ,
+                                                       typename ComputeOf<T>::type* __restrict__ colpart) {
+  typedef typename ComputeOf<T>::type C;
+  typedef typename RawVec<T, V>::type raw_t;
+  __shared__ C red[2][NT / 64][2];
+  int64_t col[S];
+  bool ok[S];
+  C gm[S][V], accb[S][V], accg[S][V], accz[S][V];
+#pragma unroll
+  for (int s = 0; s < S; s++) {
+    col[s] = ((int64_t)s * NT + threadIdx.x) * V;
+    ok[s] = col[s] < N;
+#pragma unroll
+    for (int v = 0; v < V; v++) {
+      gm[s][v] = ok[s] ? (C)gamma[col[s] + v] : (C)0;
+      accb[s][v] = 0; accg[s][v] = 0; accz[s][v] = 0;
+    }
+  }
+  raw_t ndy[S], nz[S];
+  int64_t row = blockIdx.x;
+  if (row < M) {
+#pragma unroll
+    for (int s = 0; s < S; s++) {
+      ndy[s] = ok[s] ? raw_load<T, V>(dY + row * N + col[s]) : raw_zero<T, V>();
+      nz[s] = ok[s] ? raw_load<T, V>(Z + row * N + col[s]) : raw_zero<T, V>();
+    }
+  }
+  int par = 0;
+  for (; row < M; row += gridDim.x, par ^= 1) {
+    raw_t cdy[S], cz[S];
+#pragma unroll
+    for (int s = 0; s < S; s++) { cdy[s] = ndy[s]; cz[s] = nz[s]; }
+    const int64_t nrow = row + gridDim.x;
+    if (nrow < M) {
+#pragma unroll
+      for (int s = 0; s < S; s++) {
+        if (ok[s]) { ndy[s] = raw_load<T, V>(dY + nrow * N + col[s]); nz[s] = raw_load<T, V>(Z + nrow * N + col[s]); }
+      }
+    }
+    const C mu = (C)mean[row], rs = (C)rstd[row];
+    C ah[S][V], gp[S][V], g[S][V];
+    C s1 = 0, s2 = 0;
+#pragma unroll
+    for (int s = 0; s < S; s++)
+#pragma unroll
+      for (int v = 0; v < V; v++) {
+        const C z = raw_get<T, V, C>(cz[s], v);
+        const C dy = raw_get<T, V, C>(cdy[s], v);
+        C Phi, phi;
+        Gauss<C>::eval(z, Phi, phi);
+        ah[s][v] = (z * Phi - mu) * rs;
+        gp[s][v] = Phi + z * phi;
+        g[s][v] = dy * gm[s][v];
+        s1 += g[s][v];
+        s2 += g[s][v] * ah[s][v];
+        accb[s][v] += dy;
+        accg[s][v] += dy * ah[s][v];
+      }
+    wg_sum2<C, NT / 64>(s1, s2, red[par]);
+    const C c1 = s1 / (C)N, c2 = s2 / (C)N;
+#pragma unroll
+    for (int s = 0; s < S; s++) {
+      C dz[V];
+#pragma unroll
+      for (int v = 0; v < V; v++) {
+        dz[v] = rs * (g[s][v] - c1 - ah[s][v] * c2) * gp[s][v];
+        accz[s][v] += dz[v];
+      }
+      if (ok[s]) VecIO<T, V>::store(dZ + row * N + col[s], dz);
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < S; s++)
+    if (ok[s]) {
+#pragma unroll
+      for (int v = 0; v < V; v++) {
+        colpart[((int64_t)blockIdx.x * 3 + 0) * N + col[s] + v] = accb[s][v];
+        colpart[((int64_t)blockIdx.x * 3 + 1) * N + col[s] + v] = accg[s][v];
+        colpart[((int64_t)blockIdx.x * 3 + 2) * N + col[s] + v] = accz[s][v];
+      }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// B2: colpart [groups][3][N] -> dbeta, dgamma, db.  64 consecutive columns per workgroup (coalesced),
+// the groups split over the 4 wavefronts, fp64 sums.
+template <class C>
+__global__ __launch_bounds__(256) void b2_kernel(int64_t N, int groups, const C* __restrict__ colpart,
+                                                 float* __restrict__ dbeta, float* __restrict__ dgamma,
+                                                 float* __restrict__ db) {
+  __shared__ double red[4][64];
+  const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int64_t col = (int64_t)blockIdx.x * 64 + lane;
+  const int which = blockIdx.y;
+  double acc = 0.0;
+  if (col < N)
+    for (int g = slice; g < groups; g += 4) acc += (double)colpart[((int64_t)g * 3 + which) * N + col];
+  red[slice][lane] = acc;
+  __syncthreads();
+  if (slice == 0 && col < N) {
+    const double t = red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane];
+    float* out = which == 0 ? dbeta : (which == 1 ? dgamma : db);
+    out[col] = (float)t;
+  }
+}
+
+// vector width usable for rows of length N starting at `base` (every row start must be aligned)
+template <class T> int vec_width(const void* a, const void* b, const void* c, int64_t N) {
+  constexpr int V = 16 / (int)sizeof(T);
+  const uintptr_t m = (uintptr_t)a | (uintptr_t)b | (uintptr_t)c;
+  return (N % V == 0 && m % 16 == 0) ? V : 1;
+}
+
+template <class T> void f2_impl(int64_t M, int64_t N, const void* Z, const float* mean, const float* rstd,
+                                const float* gamma, const float* beta, void* Y, hipStream_t s) {
+  constexpr int VMAX = 16 / (int)sizeof(T);
+  const int V = vec_width<T>(Z, Y, nullptr, N);
+  const int strips = (int)((N + 256 * (int64_t)V - 1) / (256 * (int64_t)V));
+  const int rows_per_wg = 16;
+  const int64_t blocks = (int64_t)strips * ((M + rows_per_wg - 1) / rows_per_wg);
+  if (V == VMAX)
+    hipLaunchKernelGGL((f2_kernel<T, VMAX>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_wg, strips,
+                       (const T*)Z, mean, rstd, gamma, beta, (T*)Y);
+  else
+    hipLaunchKernelGGL((f2_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_wg, strips,
+                       (const T*)Z, mean, rstd, gamma, beta, (T*)Y);
+}
+
+template <class T> void b1a_impl(int64_t M, int64_t N, const void* dY, const void* Z, const float* gamma,
+                                 const float* mean, const float* rstd, void* c12, hipStream_t s) {
+  typedef typename ComputeOf<T>::type C;
+  constexpr int VMAX = 16 / (int)sizeof(T);
+  const int V = vec_width<T>(dY, Z, nullptr, N);
+  const unsigned blocks = (unsigned)(M < 4096 ? M : 4096);
+  if (V == VMAX)
+    hipLaunchKernelGGL((b1a_kernel<T, VMAX>), dim3(blocks), dim3(256), 0, s, M, N, (const T*)dY, (const T*)Z, gamma,
+                       mean, rstd, (C*)c12);
+  else
+    hipLaunchKernelGGL((b1a_kernel<T, 1>), dim3(blocks), dim3(256), 0, s, M, N, (const T*)dY, (const T*)Z, gamma, mean,
+                       rstd, (C*)c12);
+}
+
+template <class T> void b1b_impl(int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Z,
+                                 const float* gamma, const float* mean, const float* rstd, const void* c12, void* dZ,
+                                 void* colpart, hipStream_t s) {
+  typedef typename ComputeOf<T>::type C;
+  constexpr int VMAX = 16 / (int)sizeof(T);
+  const int V = vec_width<T>(dY, Z, dZ, N);
+  const int strips = (int)((N + 256 * (int64_t)V - 1) / (256 * (int64_t)V));
+  const int64_t blocks = (int64_t)strips * groups;
+  if (V == VMAX)
+    hipLaunchKernelGGL((b1b_kernel<T, VMAX>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_group, strips,
+                       (const T*)dY, (const T*)Z, gamma, mean, rstd, (const C*)c12, (T*)dZ, (C*)colpart);
+  else
+    hipLaunchKernelGGL((b1b_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_group, strips,
+                       (const T*)dY, (const T*)Z, gamma, mean, rstd, (const C*)c12, (T*)dZ, (C*)colpart);
+}
+
+// Launch shapes of the fused kernel (threads NT, strips S): full-width vectors use one strip and 256, 512
+// or 1024 threads; the scalar (unaligned rows) variant also has a two-strip, 1024-thread shape.
+struct FusedShape { int nt, s; };
+inline bool fused_shape(int64_t N, int V, bool vec, FusedShape* out) {
+  const int64_t per_thread = (N + V - 1) / V;   // vectors per row
+  const int nts[3] = {256, 512, 1024};
+  for (int i = 0; i < 3; i++)
+    if (per_thread <= nts[i]) { out->nt = nts[i]; out->s = 1; return true; }
+  if (!vec && per_thread <= 2048) { out->nt = 1024; out->s = 2; return true; }
+  return false;
+}
+
+template <class T> void b1_fused_impl(int64_t M, int64_t N, int groups, const void* dY, const void* Z,
+                                      const float* gamma, const float* mean, const float* rstd, void* dZ,
+                                      void* colpart, hipStream_t s) {
+  typedef typename ComputeOf<T>::type C;
+  constexpr int VMAX = 16 / (int)sizeof(T);
+  const int V = vec_width<T>(dY, Z, dZ, N);
+  FusedShape fs;
+  if (!fused_shape(N, V, V == VMAX, &fs)) return;   // callers check b1_fused_supported first
+#define FDL_B1F(VV, SS, NTT)                                                                                         \
+  hipLaunchKernelGGL((b1_fused_kernel<T, VV, SS, NTT>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N, (const T*)dY, \
+                     (const T*)Z, gamma, mean, rstd, (T*)dZ, (C*)colpart)
+  if (V == VMAX) {
+    if (fs.nt == 256) FDL_B1F(VMAX, 1, 256); else if (fs.nt == 512) FDL_B1F(VMAX, 1, 512); else FDL_B1F(VMAX, 1, 1024);
+  } else {
+    if (fs.s == 2) FDL_B1F(1, 2, 1024);
+    else if (fs.nt == 256) FDL_B1F(1, 1, 256); else if (fs.nt == 512) FDL_B1F(1, 1, 512); else FDL_B1F(1, 1, 1024);
+  }
+#undef FDL_B1F
+}
+
+}  // namespace
+
+void launch_stats_finalize(const void* part, int tiles, int tile_w, int64_t M, int64_t N, float eps, float* mean,
+                           float* rstd, hipStream_t s) {
+  const unsigned blocks = (unsigned)((M + 255) / 256);
+  hipLaunchKernelGGL(stats_finalize_kernel, dim3(blocks), dim3(256), 0, s, (const f32x2*)part, tiles, tile_w, M, N, eps,
+                     mean, rstd);
+}
+
+void launch_f2(int dt, int64_t M, int64_t N, const void* Zsave, const float* mean, const float* rstd,
+               const float* gamma, const float* beta, void* Y, hipStream_t s) {
+  if (dt == kF32) f2_impl<float>(M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+  else f2_impl<bf16_t>(M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+}
+
+void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave, const float* gamma, const float* mean,
+                const float* rstd, void* c12, hipStream_t s) {
+  if (dt == kF32) b1a_impl<float>(M, N, dY, Zsave, gamma, mean, rstd, c12, s);
+  else b1a_impl<bf16_t>(M, N, dY, Zsave, gamma, mean, rstd, c12, s);
+}
+
+void launch_b1b(int dt, int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Zsave,
+                const float* gamma, const float* mean, const float* rstd, const void* c12, void* dZ, void* colpart,
+                hipStream_t s) {
+  if (dt == kF32) b1b_impl<float>(M, N, rows_per_group, groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+  else b1b_impl<bf16_t>(M, N, rows_per_group, groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+}
+
+// Whether rows can be read with full-width vectors depends on N only here (base pointers are required to be
+// 16-byte aligned by the entry points).
+bool b1_fused_supported(int dt, int64_t N) {
+  const int vmax = dt == kF32 ? 4 : 8;
+  const int V = (N % vmax == 0) ? vmax : 1;
+  FusedShape fs;
+  return fused_shape(N, V, V == vmax, &fs);
+}
+
+void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, const void* dY, const void* Zsave, const float* gamma,
+                     const float* mean, const float* rstd, void* dZ, void* colpart, hipStream_t s) {
+  if (dt == kF32) b1_fused_impl<float>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else b1_fused_impl<bf16_t>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+}
+
+void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
+               hipStream_t s) {
+  const dim3 grid((unsigned)((N + 63) / 64), 3);
+  if (dt == kF32) hipLaunchKernelGGL((b2_kernel<double>), grid, dim3(256), 0, s, N, groups, (const double*)colpart, dbeta, dgamma, db);
+  else hipLaunchKernelGGL((b2_kernel<float>), grid, dim3(256), 0, s, N, groups, (const float*)colpart, dbeta, dgamma, db);
+}
+
+}  // namespace fdl
