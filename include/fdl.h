@@ -111,6 +111,27 @@ fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
                         void* dX, void* dW, float* db, float* dgamma, float* dbeta,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Optional timing instrumentation (measurement protocol: the paper times kernels with warm-up runs
+ * followed by many timed runs, appendix "Kernel Evaluation Environment"; this hook lets a harness time
+ * each phase of a call with HIP events on the call's own stream).
+ *
+ * Phases: forward = F1 (GEMM + fused epilogue), FS (statistics merge), F2 (normalise);
+ *         backward = B1 (row pass), B2 (column reduce), B3 (dX GEMM), B4 (dW GEMM).
+ * `events` is a HOST array of 2*FDL_PHASE_COUNT hipEvent_t handles created by the caller (or NULL to switch
+ * the instrumentation off, the default).  While set, fdl_forward / fdl_backward record events[2*p] just
+ * before and events[2*p+1] just after the launches of phase p on the call's stream.  The array is copied;
+ * the events stay owned by the caller.  Process-wide state: not thread-safe, meant for benchmarks only.
+ * Returns FDL_ERR_SHAPE if count != 2*FDL_PHASE_COUNT (and events != NULL).
+ */
+typedef enum {
+  FDL_PHASE_F1 = 0, FDL_PHASE_FS = 1, FDL_PHASE_F2 = 2,
+  FDL_PHASE_B1 = 3, FDL_PHASE_B2 = 4, FDL_PHASE_B3 = 5, FDL_PHASE_B4 = 6,
+  FDL_PHASE_COUNT = 7
+} fdl_phase;
+
+fdl_status fdl_set_phase_events(void* const* events, int count);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,7 +18,8 @@ LIB_PATH = os.path.join(HERE, "libfdl.so")
 FDL_F32, FDL_BF16 = 0, 1
 FDL_OK, FDL_ERR_NULL, FDL_ERR_SHAPE, FDL_ERR_DTYPE, FDL_ERR_EPS, FDL_ERR_WORKSPACE, FDL_ERR_ALIGN, FDL_ERR_LAUNCH = range(8)
 
-EXPORTS = ("fdl_status_string", "fdl_workspace_bytes", "fdl_forward", "fdl_backward")
+EXPORTS = ("fdl_status_string", "fdl_workspace_bytes", "fdl_forward", "fdl_backward", "fdl_set_phase_events")
+FDL_PHASES = ("F1", "FS", "F2", "B1", "B2", "B3", "B4")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_14279_amd.build` "
@@ -35,6 +36,8 @@ _lib.fdl_forward.restype = _int
 _lib.fdl_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.fdl_backward.restype = _int
 _lib.fdl_backward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.fdl_set_phase_events.restype = _int
+_lib.fdl_set_phase_events.argtypes = [ctypes.POINTER(_vp), _int]
 
 
 class FdlError(RuntimeError):
@@ -109,5 +112,16 @@ def fdl_backward(dtype, dY, X, W, gamma, Zsave, mean, rstd, dX, dW, db, dgamma, 
     N = W.shape[0]
     st = fdl_backward_raw(dtype, M, K, N, dY, X, W, gamma, Zsave, mean, rstd, dX, dW, db, dgamma, dbeta,
                           workspace, _nbytes(workspace), _stream(stream))
+    if st != FDL_OK:
+        raise FdlError(st)
+
+
+def fdl_set_phase_events(events) -> None:
+    """events: sequence of 2*len(FDL_PHASES) hipEvent_t handles (ints), or None to switch instrumentation off."""
+    if events is None:
+        st = _lib.fdl_set_phase_events(None, 0)
+    else:
+        arr = (_vp * len(events))(*[int(e) for e in events])
+        st = _lib.fdl_set_phase_events(arr, len(events))
     if st != FDL_OK:
         raise FdlError(st)

@@ -111,6 +111,33 @@ static fdl_status check_common(fdl_dtype dt, int64_t M, int64_t K, int64_t N, co
   return FDL_OK;
 }
 
+// ---- optional per-phase event instrumentation
+static hipEvent_t g_phase_events[2 * FDL_PHASE_COUNT];
+static bool g_phase_events_on = false;
+
+extern "C" fdl_status fdl_set_phase_events(void* const* events, int count) {
+  if (events == nullptr) { g_phase_events_on = false; return FDL_OK; }
+  if (count != 2 * FDL_PHASE_COUNT) return FDL_ERR_SHAPE;
+  for (int i = 0; i < count; i++) {
+    if (events[i] == nullptr) return FDL_ERR_NULL;
+    g_phase_events[i] = static_cast<hipEvent_t>(events[i]);
+  }
+  g_phase_events_on = true;
+  return FDL_OK;
+}
+
+namespace {
+struct PhaseTimer {
+  int phase; hipStream_t s;
+  PhaseTimer(int p, hipStream_t st) : phase(p), s(st) {
+    if (g_phase_events_on) (void)hipEventRecord(g_phase_events[2 * phase], s);
+  }
+  ~PhaseTimer() {
+    if (g_phase_events_on) (void)hipEventRecord(g_phase_events[2 * phase + 1], s);
+  }
+};
+}  // namespace
+
 static fdl_status launch_status() { return hipGetLastError() == hipSuccess ? FDL_OK : FDL_ERR_LAUNCH; }
 
 extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
@@ -131,16 +158,23 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
   char* ws = static_cast<char*>(workspace);
   void* part = ws + p.off_part;
 
-  // F1
-  if (p.f1_fast) {
-    launch_fast_f1(M, K, N, X, W, b, Zsave, part, s);
-  } else {
-    GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
-    launch_generic_f1((int)dt, g, b, Zsave, part, s);
+  {
+    PhaseTimer t(FDL_PHASE_F1, s);
+    if (p.f1_fast) {
+      launch_fast_f1(M, K, N, X, W, b, Zsave, part, s);
+    } else {
+      GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
+      launch_generic_f1((int)dt, g, b, Zsave, part, s);
+    }
   }
-  // FS, F2
-  launch_stats_finalize(part, p.stat_tiles, p.stat_tile_w, M, N, eps, mean, rstd, s);
-  launch_f2((int)dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+  {
+    PhaseTimer t(FDL_PHASE_FS, s);
+    launch_stats_finalize(part, p.stat_tiles, p.stat_tile_w, M, N, eps, mean, rstd, s);
+  }
+  {
+    PhaseTimer t(FDL_PHASE_F2, s);
+    launch_f2((int)dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+  }
   return launch_status();
 }
 
@@ -173,30 +207,40 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   void* c12 = ws + p.off_c12;
   void* colpart = ws + p.off_colpart;
 
-  // B1, B2
-  if (p.b1_fused) {
-    launch_b1_fused((int)dt, M, N, p.b1_groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
-  } else {
-    launch_b1a((int)dt, M, N, dY, Zsave, gamma, mean, rstd, c12, s);
-    launch_b1b((int)dt, M, N, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+  {
+    PhaseTimer t(FDL_PHASE_B1, s);
+    if (p.b1_fused) {
+      launch_b1_fused((int)dt, M, N, p.b1_groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+    } else {
+      launch_b1a((int)dt, M, N, dY, Zsave, gamma, mean, rstd, c12, s);
+      launch_b1b((int)dt, M, N, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+    }
   }
-  launch_b2((int)dt, N, p.b1_groups, colpart, dbeta, dgamma, db, s);
-
-  // B3: dX[M,K] = dZ[M,N] W[N,K]
-  if (p.b3_fast) {
-    void* Wt = ws + p.off_wt;
-    launch_transpose_bf16(N, K, W, Wt, s);
-    launch_fast_b3(M, K, N, dZ, Wt, dX, s);
-  } else {
-    GemmDesc g = {dZ, W, M, K, N, N, K, true, false, p.b3_wb};
-    launch_generic_store((int)dt, g, dX, s);
+  {
+    PhaseTimer t(FDL_PHASE_B2, s);
+    launch_b2((int)dt, N, p.b1_groups, colpart, dbeta, dgamma, db, s);
   }
-  // B4: dW[N,K] = dZ^T[N,M] X[M,K]
-  if (p.b4_fast) {
-    launch_fast_b4(M, K, N, p.b4_split, dZ, X, dW, ws + p.off_dwpart, s);
-  } else {
-    GemmDesc g = {dZ, X, N, K, M, N, K, false, false, p.b4_wb};
-    launch_generic_store((int)dt, g, dW, s);
+  {
+    // B3: dX[M,K] = dZ[M,N] W[N,K]
+    PhaseTimer t(FDL_PHASE_B3, s);
+    if (p.b3_fast) {
+      void* Wt = ws + p.off_wt;
+      launch_transpose_bf16(N, K, W, Wt, s);
+      launch_fast_b3(M, K, N, dZ, Wt, dX, s);
+    } else {
+      GemmDesc g = {dZ, W, M, K, N, N, K, true, false, p.b3_wb};
+      launch_generic_store((int)dt, g, dX, s);
+    }
+  }
+  {
+    // B4: dW[N,K] = dZ^T[N,M] X[M,K]
+    PhaseTimer t(FDL_PHASE_B4, s);
+    if (p.b4_fast) {
+      launch_fast_b4(M, K, N, p.b4_split, dZ, X, dW, ws + p.off_dwpart, s);
+    } else {
+      GemmDesc g = {dZ, X, N, K, M, N, K, false, false, p.b4_wb};
+      launch_generic_store((int)dt, g, dW, s);
+    }
   }
   return launch_status();
 }
