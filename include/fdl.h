@@ -18,8 +18,8 @@
  * Matrices are row-major and contiguous, with no padding between rows:
  *   X [M,K]   W [N,K]   Y, Zsave, dY [M,N]   dX [M,K]   dW [N,K]
  * and are stored in the type selected by `dt`.  Vectors b, gamma, beta, db,
- * dgamma, dbeta [N] and mean, rstd [M] are always fp32.  Base pointers must be
- * 16-byte aligned; row pitches need not be.
+ * dgamma, dbeta [N] and mean, rstd [M] are always fp32.  Every base pointer
+ * (matrices and vectors) must be 16-byte aligned; row pitches need not be.
  *
  * The library allocates nothing and never synchronises: every call only
  * enqueues kernels on `hip_stream` (a hipStream_t passed as void*; NULL is the

@@ -70,7 +70,6 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.off_dz = off; off += align256((size_t)Mp * N * ts);
   q.off_c12 = off; off += align256(q.b1_fused ? 0 : (size_t)2 * Mp * cs);
   q.off_colpart = off; off += align256((size_t)q.b1_groups * 3 * N * cs);
-  q.off_wt = off; off += align256(q.b3_fast ? (size_t)K * N * ts : 0);
   q.off_dwpart = off; off += align256(q.b4_split > 1 ? (size_t)q.b4_split * N * K * 4 : 0);
   q.bwd_bytes = off;
   q.bytes = q.fwd_bytes > q.bwd_bytes ? q.fwd_bytes : q.bwd_bytes;
@@ -150,8 +149,8 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
   Plan p;
   const fdl_status st = check_common(dt, M, K, N, workspace, workspace_bytes, &p);
   if (st != FDL_OK) return st;
-  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(Zsave, 16) || !aligned(b, 4) ||
-      !aligned(gamma, 4) || !aligned(beta, 4) || !aligned(mean, 4) || !aligned(rstd, 4))
+  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(Zsave, 16) || !aligned(b, 16) ||
+      !aligned(gamma, 16) || !aligned(beta, 16) || !aligned(mean, 16) || !aligned(rstd, 16))
     return FDL_ERR_ALIGN;
   if (M == 0) return FDL_OK;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -188,8 +187,8 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   const fdl_status st = check_common(dt, M, K, N, workspace, workspace_bytes, &p);
   if (st != FDL_OK) return st;
   if (!aligned(dY, 16) || !aligned(X, 16) || !aligned(W, 16) || !aligned(Zsave, 16) || !aligned(dX, 16) ||
-      !aligned(dW, 16) || !aligned(gamma, 4) || !aligned(mean, 4) || !aligned(rstd, 4) || !aligned(db, 4) ||
-      !aligned(dgamma, 4) || !aligned(dbeta, 4))
+      !aligned(dW, 16) || !aligned(gamma, 16) || !aligned(mean, 16) || !aligned(rstd, 16) || !aligned(db, 16) ||
+      !aligned(dgamma, 16) || !aligned(dbeta, 16))
     return FDL_ERR_ALIGN;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (M == 0) {
@@ -224,9 +223,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
     // B3: dX[M,K] = dZ[M,N] W[N,K]
     PhaseTimer t(FDL_PHASE_B3, s);
     if (p.b3_fast) {
-      void* Wt = ws + p.off_wt;
-      launch_transpose_bf16(N, K, W, Wt, s);
-      launch_fast_b3(M, K, N, dZ, Wt, dX, s);
+      launch_fast_b3(M, K, N, dZ, W, dX, s);
     } else {
       GemmDesc g = {dZ, W, M, K, N, N, K, true, false, p.b3_wb};
       launch_generic_store((int)dt, g, dX, s);

@@ -36,7 +36,6 @@ struct Plan {
   size_t off_dz;          // T [M][N]
   size_t off_c12;         // C [2][M]
   size_t off_colpart;     // C [groups][3][N]
-  size_t off_wt;          // T [K][N]   (W transposed, fast B3)
   size_t off_dwpart;      // float [split][N][K]
   size_t bwd_bytes;
   size_t bytes;           // max(fwd, bwd)
@@ -85,8 +84,7 @@ bool fast_b4_supported(int64_t M, int64_t K, int64_t N);
 int fast_f1_stat_tile_w();
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
                     void* part, hipStream_t s);
-void launch_transpose_bf16(int64_t rows, int64_t cols, const void* in, void* out, hipStream_t s);
-void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* Wt, void* dX, hipStream_t s);
+void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s);
 int fast_b4_split(int64_t M, int64_t K, int64_t N);
 void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dW,
                     void* dwpart, hipStream_t s);

@@ -87,6 +87,7 @@ def test_small_and_ragged_shapes(dtype, shape):
 
 @pytest.mark.parametrize("dtype,shape", [
     ("bf16", (512, 256, 512)), ("bf16", (1024, 512, 768)), ("bf16", (256, 1024, 256)), ("bf16", (768, 128, 1280)),
+    ("bf16", (256, 256, 256)), ("bf16", (2048, 256, 256)), ("bf16", (4096, 512, 1024)), ("bf16", (2304, 768, 2560)),
     ("f32", (384, 128, 1024)), ("f32", (100, 64, 4100)),      # f32 rows longer than the fused row kernel holds
     ("bf16", (24, 16, 8200)), ("bf16", (16, 8, 2051)),        # bf16 rows beyond the fused kernel (aligned / unaligned)
     ("f32", (8, 8, 2051)),
