@@ -25,19 +25,26 @@ if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2509_14279_amd.build` "
                       "(there is no fallback path)")
 
-_lib = ctypes.CDLL(LIB_PATH)
 _vp, _i64, _sz, _f32, _int = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_float, ctypes.c_int
 
-_lib.fdl_status_string.restype = ctypes.c_char_p
-_lib.fdl_status_string.argtypes = [_int]
-_lib.fdl_workspace_bytes.restype = _sz
-_lib.fdl_workspace_bytes.argtypes = [_int, _i64, _i64, _i64]
-_lib.fdl_forward.restype = _int
-_lib.fdl_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-_lib.fdl_backward.restype = _int
-_lib.fdl_backward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
-_lib.fdl_set_phase_events.restype = _int
-_lib.fdl_set_phase_events.argtypes = [ctypes.POINTER(_vp), _int]
+
+def _bind(lib):
+    """Declare the C signatures of include/fdl.h on a loaded library."""
+    lib.fdl_status_string.restype = ctypes.c_char_p
+    lib.fdl_status_string.argtypes = [_int]
+    lib.fdl_workspace_bytes.restype = _sz
+    lib.fdl_workspace_bytes.argtypes = [_int, _i64, _i64, _i64]
+    lib.fdl_forward.restype = _int
+    lib.fdl_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.fdl_backward.restype = _int
+    lib.fdl_backward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                 _vp, _sz, _vp]
+    lib.fdl_set_phase_events.restype = _int
+    lib.fdl_set_phase_events.argtypes = [ctypes.POINTER(_vp), _int]
+    return lib
+
+
+_lib = _bind(ctypes.CDLL(LIB_PATH))
 
 
 class FdlError(RuntimeError):

@@ -13,8 +13,9 @@
 // (the linear layer's forward, grad-input and grad-weight products of the paper's linear tasks.)
 //
 // Workgroup: 256 threads = 4 waves (2 x 2), one per SIMD; block tile 256 x 256, wave tile 128 x 128 as 4 x 4
-// v_mfma_f32_32x32x16_bf16 blocks (256 fp32 accumulators per lane); reduction slices of 64, two LDS stages of
-// 64 KB filled by direct global->LDS loads (16 bytes per lane) that stay in flight during the MFMAs.
+// v_mfma_f32_32x32x16_bf16 blocks (256 fp32 accumulators per lane, held in AGPRs); reduction slices of 64, two
+// LDS stages of 64 KB filled by direct global->LDS loads (16 bytes per lane, no staging registers) that stay in
+// flight for a whole slice time while the MFMAs of the other stage run.
 //
 // LDS tile layouts (both XOR-swizzled by choosing which global chunk a lane fetches, since a direct load
 // lands at base + lane*16):
@@ -170,8 +171,14 @@ void gemm_bf16_kernel(FastParams p) {
 #pragma unroll
       for (int r = 0; r < 16; r++) acc[a][b][r] = 0.0f;
 
+  const int last = p.nkt - 1;
   lp.issue(pbase, p.ldp, wave, lds0);
   lq.issue(qbase, p.ldq, wave, lds0 + kOperandBytes);
+  {
+    const int k1 = 1 < last ? 1 : last;
+    lp.issue(pbase + k1 * pstep, p.ldp, wave, lds0 + kStageBytes);
+    lq.issue(qbase + k1 * qstep, p.ldq, wave, lds0 + kStageBytes + kOperandBytes);
+  }
   wait_dma();
   __syncthreads();
 
@@ -187,19 +194,21 @@ void gemm_bf16_kernel(FastParams p) {
 
   for (int kt = 0; kt < p.nkt; kt++) {
     const int cur = kt & 1;
-    // The slice after the last one does not exist: the last iteration re-fetches its own slice into the idle
-    // stage (never read) so that the loop body is branch-free.
-    const int ktn = kt + 1 < p.nkt ? kt + 1 : kt;
-    const uint32_t nxt = lds0 + (uint32_t)(cur ^ 1) * kStageBytes;
-    const bf16_t* pn = pbase + (int64_t)ktn * pstep;
-    const bf16_t* qn = qbase + (int64_t)ktn * qstep;
+    // Slice kt+2 is fetched into this slice's own stage as soon as the barrier below has shown that every wave
+    // holds its last fragments of slice kt in registers: the direct loads then have one whole slice time (the
+    // most two stages allow) before the next barrier needs them.  Slices past the end are clamped to the last
+    // one (fetched again, never read) so that the loop body is branch-free.
+    const int k2 = kt + 2 < last ? kt + 2 : last;
+    const uint32_t own = lds0 + (uint32_t)cur * kStageBytes;
+    const bf16_t* pn = pbase + (int64_t)k2 * pstep;
+    const bf16_t* qn = qbase + (int64_t)k2 * qstep;
     const lds_char* tp = lds + cur * kStageBytes;
     const lds_char* tq = tp + kOperandBytes;
     const lds_char* np_ = lds + (cur ^ 1) * kStageBytes;
     const lds_char* nq_ = np_ + kOperandBytes;
     // Issue order is pinned by hand (a scheduling barrier after every step): MFMA t of a sub-slice is followed by
-    // a fragment read of the next sub-slice (even t) or, during sub-slice 0, by one direct load of the next
-    // slice (every t), so neither the LDS reads nor the global loads ever stall the matrix pipe for long.
+    // a fragment read of the next sub-slice (even t) and, in the last sub-slice, by one direct load, so neither
+    // the LDS reads nor the global loads keep the matrix pipe waiting for long.
 #pragma unroll
     for (int kk = 0; kk < 4; kk++) {
       const int use = kk & 1, fill = use ^ 1;
@@ -224,14 +233,15 @@ void gemm_bf16_kernel(FastParams p) {
           else pf[fill][slot - 4] = fp.load(rp, slot - 4, rk);
           __builtin_amdgcn_sched_barrier(0);
         }
-        if (kk == 0) {
-          if (t < 8) lp.issue1(t, pn, p.ldp, wave, nxt);
-          else lq.issue1(t - 8, qn, p.ldq, wave, nxt + kOperandBytes);
+        if (kk == 3) {
+          if (t < 8) lp.issue1(t, pn, p.ldp, wave, own);
+          else lq.issue1(t - 8, qn, p.ldq, wave, own + kOperandBytes);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
   }
+  wait_dma();   // the clamped re-fetches of the last two iterations must land before the workgroup may retire
 
   // ------------------------------------------------------------------ epilogue
   // accumulator register r of block (a, b): i = a*32 + (r/4)*8 + (lane/32)*4 + r%4, j = b*32 + lane%32
