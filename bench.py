@@ -52,6 +52,38 @@ class HipEvents:
         self.hip.hipEventDestroy(e)
 
 
+def sources_sha256() -> str:
+    """Hash of the kernel sources: byte counters taken for one build are not quoted for another."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2509_14279_amd", "csrc")
+    for f in sorted(os.listdir(d)):
+        if f.endswith((".hip", ".h")):
+            h.update(f.encode())
+            h.update(open(os.path.join(d, f), "rb").read())
+    return h.hexdigest()
+
+
+def measured_traffic(cfg_name: str, phase: str):
+    """HBM-side bytes per launch of `phase` from the committed rocprofv3 counter summary, or None if the
+    kernels changed since the counters were taken (or none were taken for this workload)."""
+    path = os.path.join(ROOT, "profiles", "cfg4_bf16_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("TRAFFIC_JSON:"):
+                t = json.loads(line[len("TRAFFIC_JSON:"):])
+                if t.get("workload") != cfg_name or t.get("sources_sha256") != sources_sha256():
+                    return None
+                ph = t["phases"].get(phase)
+                if not ph:
+                    return None
+                return {"fetch_bytes": round(ph.get("fetch_bytes", 0.0)), "write_bytes": round(ph.get("write_bytes", 0.0)),
+                        "total_bytes": round(ph.get("fetch_bytes", 0.0) + ph.get("write_bytes", 0.0))}
+    except OSError:
+        pass
+    return None
+
+
 def phase_work(cfg):
     """Algorithmic work per launch of each phase: (kind, amount) with flop for GEMMs, bytes for streaming."""
     M, K, N = cfg.M, cfg.K, cfg.N
@@ -122,6 +154,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy a few times (reference point for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on exactly one GPU (got --gpus {args.gpus}); "
@@ -153,6 +187,15 @@ def main():
     def step():
         api.fdl_forward(cfg.dtype, d["X"], d["W"], d["b"], d["gamma"], d["beta"], cfg.eps, Y, Z, mean, rstd, ws, stream)
         api.fdl_backward(cfg.dtype, d["dY"], d["X"], d["W"], d["gamma"], Z, mean, rstd, dX, dW, db, dg, dbt, ws, stream)
+
+    if args.copy_calibration:
+        # a plain copy of known size: 1 GiB read + 1 GiB written per launch (elementwise copy kernel)
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -195,11 +238,11 @@ def main():
     if kind == "flop":
         ach = amount / (phase_ms[dom] * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_TFLOPS[cfg.dtype],
-                    "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS[cfg.dtype], 4), "traffic": None}
+                    "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS[cfg.dtype], 4), "traffic": measured_traffic(cfg.name, dom)}
     else:
         ach = amount / (phase_ms[dom] * 1e-3) / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": measured_traffic(cfg.name, dom)}
 
     out = {
         "metric": "fused fwd+bwd TFLOP/s (6*M*N*K flop per step) on 1 MI355X",
