@@ -54,40 +54,59 @@ typedef __attribute__((address_space(3))) char lds_char;
 typedef __attribute__((ext_vector_type(4))) short short4_;
 typedef __attribute__((address_space(3))) short4_ lds_short4;
 
-// 16 bytes per lane, global -> LDS, no registers: lane l's data lands at lds_addr + 16 l.
-// voff: per-lane byte offset, sbase: wave-uniform global base, lds_addr: wave-uniform LDS byte address.
-__device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(sbase), "s"(lds_addr) : "memory", "m0");
+// 16 bytes per lane, global -> LDS, no registers: lane l's data lands at (lds_base + LDS_OFF) + 16 l.
+// voff: per-lane byte offset, sbase: wave-uniform global base, lds_base: wave-uniform LDS byte address.
+// M0 carries the LDS address; one wait state separates the SALU write of M0 from the load that reads it.
+template <int LDS_OFF>
+__device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base), "n"(LDS_OFF) : "memory", "m0", "scc");
 }
 __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 template <bool RM> struct Loader {
-  // Per-lane byte offsets (constant over the reduction loop) and the per-instruction scalar stride.
-  // Eight instructions per wave fill this wave's quarter of the 32 KB operand tile.
-  uint32_t voff[2];
+  // voff[q]: per-lane byte offset of instruction q (constant over the reduction loop).  Eight instructions per
+  // wave fill this wave's quarter of the 32 KB operand tile; the only per-slice scalar work is one base pointer.
+  uint32_t voff[8];
   __device__ __forceinline__ void init(int lane, int64_t ld) {
-    if (RM) {
-      // instruction q covers r-rows 2q, 2q+1 (of this wave's 16); lane: r-row h = lane/32, slot lane%32
-      const int h = lane >> 5, slot = lane & 31;
-      const int c_even = slot ^ (h << 1);          // (2q + h) & 3 = h      for even q
-      const int c_odd = slot ^ ((2 + h) << 1);     //               = 2 + h  for odd q
-      voff[0] = (uint32_t)(h * ld * 2 + c_even * 16);
-      voff[1] = (uint32_t)(h * ld * 2 + c_odd * 16);
-    } else {
-      // instruction q covers rows 8q..8q+7 (of this wave's 64); lane: row lane/8, slot lane%8
-      const int w = lane >> 3, slot = lane & 7;
-      voff[0] = voff[1] = (uint32_t)(w * ld * 2 + ((slot ^ w) * 16));
+#pragma unroll
+    for (int q = 0; q < 8; q++) {
+      if (RM) {
+        // instruction q covers r-rows 2q, 2q+1 (of this wave's 16); lane: r-row 2q + h, h = lane/32, slot lane%32
+        const int h = lane >> 5, slot = lane & 31;
+        const int c = slot ^ (((2 * q + h) & 3) << 1);
+        voff[q] = (uint32_t)((int64_t)(2 * q + h) * ld * 2 + c * 16);
+      } else {
+        // instruction q covers rows 8q..8q+7 (of this wave's 64); lane: row 8q + w, w = lane/8, slot lane%8
+        const int w = lane >> 3, slot = lane & 7;
+        voff[q] = (uint32_t)((int64_t)(8 * q + w) * ld * 2 + ((slot ^ w) * 16));
+      }
     }
   }
-  // base: element (row/col origin of the block tile, first r of the slice); lds: operand tile address
-  __device__ __forceinline__ void issue1(int q, const bf16_t* base, int64_t ld, int wave, uint32_t lds) const {
-    const bf16_t* sb = RM ? base + (int64_t)(wave * 16 + q * 2) * ld : base + (int64_t)(wave * 64 + q * 8) * ld;
-    dma16(voff[q & 1], sb, lds + (uint32_t)(wave * 8 + q) * 1024u);
+  // first element this wave fetches of the slice that starts at `base` (block tile origin, first r of the slice)
+  __device__ __forceinline__ const bf16_t* wave_base(const bf16_t* base, int64_t ld, int wave) const {
+    return RM ? base + (int64_t)(wave * 16) * ld : base + (int64_t)(wave * 64) * ld;
   }
-  __device__ __forceinline__ void issue(const bf16_t* base, int64_t ld, int wave, uint32_t lds) const {
-#pragma unroll
-    for (int q = 0; q < 8; q++) issue1(q, base, ld, wave, lds);
+  // wbase: wave_base(...) of the slice; wlds: LDS address of this wave's quarter of the operand tile
+  template <int Q> __device__ __forceinline__ void issue1(const bf16_t* wbase, uint32_t wlds) const {
+    dma16<Q * 1024>(voff[Q], wbase, wlds);
+  }
+  // q is a compile-time constant at every call site once the surrounding loop is unrolled
+  __device__ __forceinline__ void issue_q(int q, const bf16_t* wbase, uint32_t wlds) const {
+    switch (q) {
+      case 0: issue1<0>(wbase, wlds); break;
+      case 1: issue1<1>(wbase, wlds); break;
+      case 2: issue1<2>(wbase, wlds); break;
+      case 3: issue1<3>(wbase, wlds); break;
+      case 4: issue1<4>(wbase, wlds); break;
+      case 5: issue1<5>(wbase, wlds); break;
+      case 6: issue1<6>(wbase, wlds); break;
+      default: issue1<7>(wbase, wlds); break;
+    }
+  }
+  __device__ __forceinline__ void issue(const bf16_t* wbase, uint32_t wlds) const {
+    issue1<0>(wbase, wlds); issue1<1>(wbase, wlds); issue1<2>(wbase, wlds); issue1<3>(wbase, wlds);
+    issue1<4>(wbase, wlds); issue1<5>(wbase, wlds); issue1<6>(wbase, wlds); issue1<7>(wbase, wlds);
   }
 };
 
@@ -172,12 +191,13 @@ void gemm_bf16_kernel(FastParams p) {
       for (int r = 0; r < 16; r++) acc[a][b][r] = 0.0f;
 
   const int last = p.nkt - 1;
-  lp.issue(pbase, p.ldp, wave, lds0);
-  lq.issue(qbase, p.ldq, wave, lds0 + kOperandBytes);
+  const uint32_t wlds = lds0 + (uint32_t)wave * 8192u;      // this wave's quarter of an operand tile
+  lp.issue(lp.wave_base(pbase, p.ldp, wave), wlds);
+  lq.issue(lq.wave_base(qbase, p.ldq, wave), wlds + kOperandBytes);
   {
     const int k1 = 1 < last ? 1 : last;
-    lp.issue(pbase + k1 * pstep, p.ldp, wave, lds0 + kStageBytes);
-    lq.issue(qbase + k1 * qstep, p.ldq, wave, lds0 + kStageBytes + kOperandBytes);
+    lp.issue(lp.wave_base(pbase + k1 * pstep, p.ldp, wave), wlds + kStageBytes);
+    lq.issue(lq.wave_base(qbase + k1 * qstep, p.ldq, wave), wlds + kStageBytes + kOperandBytes);
   }
   wait_dma();
   __syncthreads();
@@ -199,9 +219,9 @@ void gemm_bf16_kernel(FastParams p) {
     // most two stages allow) before the next barrier needs them.  Slices past the end are clamped to the last
     // one (fetched again, never read) so that the loop body is branch-free.
     const int k2 = kt + 2 < last ? kt + 2 : last;
-    const uint32_t own = lds0 + (uint32_t)cur * kStageBytes;
-    const bf16_t* pn = pbase + (int64_t)k2 * pstep;
-    const bf16_t* qn = qbase + (int64_t)k2 * qstep;
+    const uint32_t own = wlds + (uint32_t)cur * kStageBytes;
+    const bf16_t* pn = lp.wave_base(pbase + (int64_t)k2 * pstep, p.ldp, wave);
+    const bf16_t* qn = lq.wave_base(qbase + (int64_t)k2 * qstep, p.ldq, wave);
     const lds_char* tp = lds + cur * kStageBytes;
     const lds_char* tq = tp + kOperandBytes;
     const lds_char* np_ = lds + (cur ^ 1) * kStageBytes;
@@ -234,8 +254,8 @@ void gemm_bf16_kernel(FastParams p) {
           __builtin_amdgcn_sched_barrier(0);
         }
         if (kk == 3) {
-          if (t < 8) lp.issue1(t, pn, p.ldp, wave, own);
-          else lq.issue1(t - 8, qn, p.ldq, wave, own + kOperandBytes);
+          if (t < 8) lp.issue_q(t, pn, own);
+          else lq.issue_q(t - 8, qn, own + kOperandBytes);
           __builtin_amdgcn_sched_barrier(0);
         }
       }

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(256) void b1b_kernel(int64_t M, int64_t N, int rows
     for (int v = 0; v < V; v++) {
       C Phi, phi;
       Gauss<C>::eval(z[v], Phi, phi);
-      const C ah = (z[v] * Phi - mu) * rs;
+      const C ah = (Gauss<C>::gelu_of(z[v], Phi) - mu) * rs;
       const C g = dy[v] * gm[v];
       dz[v] = rs * (g - c1 - ah * c2) * (Phi + z[v] * phi);
       accb[v] += dy[v];
@@ -159,8 +159,8 @@ __global__ __launch_bounds__(256) void b1b_kernel(int64_t M, int64_t N, int rows
 
 // ------------------------------------------------------------------------------------------------
 // B1 fused: one pass, the row held in registers (S strips of NT*V columns, NT threads).  A workgroup walks rows
-// blockIdx.x, blockIdx.x + gridDim.x, ... ; the next row's loads are issued before the current row's
-// arithmetic; one barrier per row (the LDS exchange slot alternates with the row parity).
+// blockIdx.x, blockIdx.x + gridDim.x, ... ; two rows of loads are in flight while a row is processed; one barrier
+// per row (the LDS exchange slot alternates between consecutive rows).
 template <class T, int V> struct RawVec;
 template <> struct RawVec<float, 4> { typedef f32x4 type; };
 template <> struct RawVec<float, 1> { typedef float type; };
@@ -201,27 +201,26 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
       accb[s][v] = 0; accg[s][v] = 0; accz[s][v] = 0;
     }
   }
-  raw_t ndy[S], nz[S];
-  int64_t row = blockIdx.x;
-  if (row < M) {
-#pragma unroll
-    for (int s = 0; s < S; s++) {
-      ndy[s] = ok[s] ? raw_load<T, V>(dY + row * N + col[s]) : raw_zero<T, V>();
-      nz[s] = ok[s] ? raw_load<T, V>(Z + row * N + col[s]) : raw_zero<T, V>();
-    }
-  }
-  int par = 0;
-  for (; row < M; row += gridDim.x, par ^= 1) {
-    raw_t cdy[S], cz[S];
-#pragma unroll
-    for (int s = 0; s < S; s++) { cdy[s] = ndy[s]; cz[s] = nz[s]; }
-    const int64_t nrow = row + gridDim.x;
-    if (nrow < M) {
+  // Two rows are kept in flight: buffers 0 and 1 hold the raw rows r and r + G (G = gridDim.x); as soon as a
+  // buffer has been unpacked its refill with row r + 2G is issued, ahead of that row's barrier and second phase.
+  raw_t bdy[2][S], bz[2][S];
+  const int64_t G = gridDim.x;
+  auto fetch = [&](int buf, int64_t r) {
+    if (r < M) {
 #pragma unroll
       for (int s = 0; s < S; s++) {
-        if (ok[s]) { ndy[s] = raw_load<T, V>(dY + nrow * N + col[s]); nz[s] = raw_load<T, V>(Z + nrow * N + col[s]); }
+        if (ok[s]) { bdy[buf][s] = raw_load<T, V>(dY + r * N + col[s]); bz[buf][s] = raw_load<T, V>(Z + r * N + col[s]); }
       }
     }
+  };
+#pragma unroll
+  for (int buf = 0; buf < 2; buf++)
+#pragma unroll
+    for (int s = 0; s < S; s++) { bdy[buf][s] = raw_zero<T, V>(); bz[buf][s] = raw_zero<T, V>(); }
+  fetch(0, blockIdx.x);
+  fetch(1, blockIdx.x + G);
+
+  auto process = [&](int buf, int64_t row) {
     const C mu = (C)mean[row], rs = (C)rstd[row];
     C ah[S][V], gp[S][V], g[S][V];
     C s1 = 0, s2 = 0;
@@ -229,30 +228,35 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
     for (int s = 0; s < S; s++)
 #pragma unroll
       for (int v = 0; v < V; v++) {
-        const C z = raw_get<T, V, C>(cz[s], v);
-        const C dy = raw_get<T, V, C>(cdy[s], v);
+        const C z = raw_get<T, V, C>(bz[buf][s], v);
+        const C dy = raw_get<T, V, C>(bdy[buf][s], v);
         C Phi, phi;
         Gauss<C>::eval(z, Phi, phi);
-        ah[s][v] = (z * Phi - mu) * rs;
-        gp[s][v] = Phi + z * phi;
+        ah[s][v] = (Gauss<C>::gelu_of(z, Phi) - mu) * rs;
+        gp[s][v] = (Phi + z * phi) * rs;
         g[s][v] = dy * gm[s][v];
         s1 += g[s][v];
         s2 += g[s][v] * ah[s][v];
         accb[s][v] += dy;
         accg[s][v] += dy * ah[s][v];
       }
-    wg_sum2<C, NT / 64>(s1, s2, red[par]);
+    fetch(buf, row + 2 * G);
+    wg_sum2<C, NT / 64>(s1, s2, red[buf]);
     const C c1 = s1 / (C)N, c2 = s2 / (C)N;
 #pragma unroll
     for (int s = 0; s < S; s++) {
       C dz[V];
 #pragma unroll
       for (int v = 0; v < V; v++) {
-        dz[v] = rs * (g[s][v] - c1 - ah[s][v] * c2) * gp[s][v];
+        dz[v] = (g[s][v] - c1 - ah[s][v] * c2) * gp[s][v];
         accz[s][v] += dz[v];
       }
       if (ok[s]) VecIO<T, V>::store(dZ + row * N + col[s], dz);
     }
+  };
+  for (int64_t row = blockIdx.x; row < M; row += 2 * G) {
+    process(0, row);
+    if (row + G < M) process(1, row + G);
   }
 #pragma unroll
   for (int s = 0; s < S; s++)
