@@ -30,7 +30,10 @@ class HipEvents:
     """Plain hipEvent_t handles through libamdhip64 (torch events are bound to torch's own streams)."""
 
     def __init__(self):
-        self.hip = ctypes.CDLL("libamdhip64.so")
+        # the copy of the runtime this process already runs on (torch's), never a second one found by name
+        loaded = sorted({ln.split()[-1] for ln in open("/proc/self/maps") if "libamdhip64" in ln})
+        assert len(loaded) == 1, f"expected exactly one HIP runtime in the process, found {loaded}"
+        self.hip = ctypes.CDLL(loaded[0])
         self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
         self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
         self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]

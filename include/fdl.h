@@ -31,7 +31,9 @@
  *
  * Errors are reported by return code; every argument check happens before any
  * device call, so a rejected call has touched nothing.  FDL_ERR_LAUNCH reports
- * a HIP launch error (hipGetLastError after the launches).
+ * a HIP launch error (hipGetLastError after the launches; the reason is printed
+ * to stderr).  An accepted call first clears the calling thread's HIP last-error
+ * state, so an error left behind by earlier, unrelated HIP calls is not reported.
  */
 #ifndef FDL_H_
 #define FDL_H_

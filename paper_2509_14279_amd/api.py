@@ -12,6 +12,12 @@ import ctypes
 import os
 from typing import Optional, Union
 
+# torch must be loaded before libfdl.so.  The torch wheel carries its own HIP runtime under the same shared-object
+# name as the system one the library was linked against; the dynamic loader keeps whichever copy arrives first for
+# both.  Loading the library first would leave torch's allocations and streams and the library's kernels in two
+# different runtimes, and every launch on a torch buffer then fails with a device error.
+import torch  # noqa: F401  (import order matters)
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libfdl.so")
 

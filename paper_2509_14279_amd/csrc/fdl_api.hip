@@ -4,6 +4,7 @@
 #include "internal.h"
 
 #include <cmath>
+#include <cstdio>
 
 namespace fdl {
 namespace {
@@ -137,7 +138,16 @@ struct PhaseTimer {
 };
 }  // namespace
 
-static fdl_status launch_status() { return hipGetLastError() == hipSuccess ? FDL_OK : FDL_ERR_LAUNCH; }
+// The HIP "last error" is per-thread state shared with everything else the caller does on this thread (an
+// allocator that probed and recovered from an out-of-memory condition leaves it set): it is cleared on entry so
+// that only this call's launches are reported, and the reason of a failed launch goes to stderr.
+static void clear_stale_error() { (void)hipGetLastError(); }
+static fdl_status launch_status() {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return FDL_OK;
+  fprintf(stderr, "libfdl: kernel launch failed: %s\n", hipGetErrorString(e));
+  return FDL_ERR_LAUNCH;
+}
 
 extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
                                   const float* b, const float* gamma, const float* beta, float eps, void* Y,
@@ -153,6 +163,7 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
       !aligned(gamma, 16) || !aligned(beta, 16) || !aligned(mean, 16) || !aligned(rstd, 16))
     return FDL_ERR_ALIGN;
   if (M == 0) return FDL_OK;
+  clear_stale_error();
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   void* part = ws + p.off_part;
@@ -190,6 +201,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
       !aligned(dW, 16) || !aligned(gamma, 16) || !aligned(mean, 16) || !aligned(rstd, 16) || !aligned(db, 16) ||
       !aligned(dgamma, 16) || !aligned(dbeta, 16))
     return FDL_ERR_ALIGN;
+  clear_stale_error();
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   if (M == 0) {
     // no rows: every sum over rows is empty

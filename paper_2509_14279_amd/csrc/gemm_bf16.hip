@@ -13,15 +13,18 @@
 // (the linear layer's forward, grad-input and grad-weight products of the paper's linear tasks.)
 //
 // Workgroup: 256 threads = 4 waves (2 x 2), one per SIMD; block tile 256 x 256, wave tile 128 x 128 as 4 x 4
-// v_mfma_f32_32x32x16_bf16 blocks (256 fp32 accumulators per lane, held in AGPRs); reduction slices of 64, two
-// LDS stages of 64 KB filled by direct global->LDS loads (16 bytes per lane, no staging registers) that stay in
-// flight for a whole slice time while the MFMAs of the other stage run.
+// v_mfma_f32_32x32x16_bf16 blocks (256 fp32 accumulators per lane, held in AGPRs).  The reduction runs in slices of
+// BK through NS LDS stages (BK x NS = 64 x 2 or 32 x 4, 128 KB either way) filled by direct global->LDS loads
+// (16 bytes per lane, no staging registers); the loads of slice kt+NS are issued as soon as slice kt's stage is
+// released and stay in flight for NS-1 slice times while the MFMAs of the other stages run.  Workgroups are
+// persistent (one per CU): the first slices of a workgroup's next tile are fetched during the last slices of its
+// current one, and output tiles leave through a small LDS staging area as 256-byte row segments.
 //
-// LDS tile layouts (both XOR-swizzled by choosing which global chunk a lane fetches, since a direct load
-// lands at base + lane*16):
-//   r-contiguous operand: [256 rows][8 chunks of 16 B]; chunk c of row w sits in slot c ^ (w & 7); fragments
-//       are read with ds_read_b128 (8 consecutive r for the lane's row).
-//   r-major operand:      [64 r-rows][32 chunks of 16 B]; chunk c of r-row w sits in slot c ^ ((w & 3) << 1);
+// LDS tile layouts (XOR-swizzled by choosing which global chunk a lane fetches, since a direct load lands at
+// base + lane*16):
+//   r-contiguous operand: [256 rows][BK/8 chunks of 16 B]; BK = 64: chunk c of row w in slot c ^ (w & 7);
+//       BK = 32: slot c ^ ((w >> 1) & 3); fragments are read with ds_read_b128 (8 consecutive r of the lane's row).
+//   r-major operand:      [BK r-rows][32 chunks of 16 B]; chunk c of r-row w sits in slot c ^ ((w & 3) << 1);
 //       fragments are read with the transposing ds_read_b64_tr_b16 (4 consecutive r for the lane's column).
 #include "common.hip.h"
 #include "internal.h"
@@ -30,10 +33,17 @@ namespace fdl {
 namespace {
 
 constexpr int kTile = 256;
-constexpr int kBK = 64;
-constexpr int kOperandBytes = kTile * kBK * 2;   // 32 KB
-constexpr int kStageBytes = 2 * kOperandBytes;   // 64 KB
-constexpr int kLdsBytes = 2 * kStageBytes;       // 128 KB
+constexpr int kLdsStages = 128 * 1024;           // all pipeline stages together (2 x 64 KB or 4 x 32 KB)
+constexpr int kLdsBytes = kLdsStages + 4 * 8192; // + 8 KB per wave for the output block rows = 160 KB
+
+// Geometry of one pipeline configuration: reduction slices of BK, NS stages.
+template <int BK> struct Geo {
+  static constexpr int kSub = BK / 16;                    // MFMA sub-slices per slice
+  static constexpr int kOperandBytes = kTile * BK * 2;    // one operand tile of one slice
+  static constexpr int kStageBytes = 2 * kOperandBytes;   // P tile then Q tile
+  static constexpr int kDpw = BK / 8;                     // direct-load instructions per operand, wave and slice
+  static constexpr int kWaveBytes = kOperandBytes / 4;    // each wave fills a quarter of an operand tile
+};
 
 enum { EPI_STORE = 0, EPI_F1 = 1 };
 
@@ -53,6 +63,8 @@ struct FastParams {
 typedef __attribute__((address_space(3))) char lds_char;
 typedef __attribute__((ext_vector_type(4))) short short4_;
 typedef __attribute__((address_space(3))) short4_ lds_short4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 
 // 16 bytes per lane, global -> LDS, no registers: lane l's data lands at (lds_base + LDS_OFF) + 16 l.
 // voff: per-lane byte offset, sbase: wave-uniform global base, lds_base: wave-uniform LDS byte address.
@@ -62,34 +74,40 @@ __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t
   asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :: "v"(voff), "s"(sbase), "s"(lds_base), "n"(LDS_OFF) : "memory", "m0", "scc");
 }
-__device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// wait until at most N vector-memory operations of this wave are outstanding (loads complete in order)
+template <int N> __device__ __forceinline__ void wait_dma() { asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory"); }
 
-template <bool RM> struct Loader {
-  // voff[q]: per-lane byte offset of instruction q (constant over the reduction loop).  Eight instructions per
-  // wave fill this wave's quarter of the 32 KB operand tile; the only per-slice scalar work is one base pointer.
-  uint32_t voff[8];
+template <bool RM, int BK> struct Loader {
+  // voff[q]: per-lane byte offset of instruction q (constant over the reduction loop).  kDpw instructions per wave
+  // fill this wave's quarter of the operand tile; the only per-slice scalar work is one base pointer.
+  static constexpr int kDpw = Geo<BK>::kDpw;
+  uint32_t voff[kDpw];
   __device__ __forceinline__ void init(int lane, int64_t ld) {
 #pragma unroll
-    for (int q = 0; q < 8; q++) {
+    for (int q = 0; q < kDpw; q++) {
       if (RM) {
-        // instruction q covers r-rows 2q, 2q+1 (of this wave's 16); lane: r-row 2q + h, h = lane/32, slot lane%32
+        // instruction q covers r-rows 2q, 2q+1 of this wave's BK/4; lane: r-row 2q + h, h = lane/32, slot lane%32
         const int h = lane >> 5, slot = lane & 31;
         const int c = slot ^ (((2 * q + h) & 3) << 1);
         voff[q] = (uint32_t)((int64_t)(2 * q + h) * ld * 2 + c * 16);
-      } else {
-        // instruction q covers rows 8q..8q+7 (of this wave's 64); lane: row 8q + w, w = lane/8, slot lane%8
+      } else if (BK == 64) {
+        // instruction q covers rows 8q..8q+7 of this wave's 64; lane: row 8q + w, w = lane/8, slot lane%8
         const int w = lane >> 3, slot = lane & 7;
         voff[q] = (uint32_t)((int64_t)(8 * q + w) * ld * 2 + ((slot ^ w) * 16));
+      } else {
+        // BK = 32: instruction q covers rows 16q..16q+15 of this wave's 64; lane: row 16q + w, w = lane/4, slot lane%4
+        const int w = lane >> 2, slot = lane & 3;
+        voff[q] = (uint32_t)((int64_t)(16 * q + w) * ld * 2 + ((slot ^ ((w >> 1) & 3)) * 16));
       }
     }
   }
   // first element this wave fetches of the slice that starts at `base` (block tile origin, first r of the slice)
   __device__ __forceinline__ const bf16_t* wave_base(const bf16_t* base, int64_t ld, int wave) const {
-    return RM ? base + (int64_t)(wave * 16) * ld : base + (int64_t)(wave * 64) * ld;
+    return RM ? base + (int64_t)(wave * (BK / 4)) * ld : base + (int64_t)(wave * 64) * ld;
   }
   // wbase: wave_base(...) of the slice; wlds: LDS address of this wave's quarter of the operand tile
   template <int Q> __device__ __forceinline__ void issue1(const bf16_t* wbase, uint32_t wlds) const {
-    dma16<Q * 1024>(voff[Q], wbase, wlds);
+    dma16<Q * 1024>(voff[Q < kDpw ? Q : 0], wbase, wlds);
   }
   // q is a compile-time constant at every call site once the surrounding loop is unrolled
   __device__ __forceinline__ void issue_q(int q, const bf16_t* wbase, uint32_t wlds) const {
@@ -98,21 +116,21 @@ template <bool RM> struct Loader {
       case 1: issue1<1>(wbase, wlds); break;
       case 2: issue1<2>(wbase, wlds); break;
       case 3: issue1<3>(wbase, wlds); break;
-      case 4: issue1<4>(wbase, wlds); break;
-      case 5: issue1<5>(wbase, wlds); break;
-      case 6: issue1<6>(wbase, wlds); break;
-      default: issue1<7>(wbase, wlds); break;
+      case 4: if (kDpw > 4) issue1<4>(wbase, wlds); break;
+      case 5: if (kDpw > 4) issue1<5>(wbase, wlds); break;
+      case 6: if (kDpw > 4) issue1<6>(wbase, wlds); break;
+      default: if (kDpw > 4) issue1<7>(wbase, wlds); break;
     }
   }
   __device__ __forceinline__ void issue(const bf16_t* wbase, uint32_t wlds) const {
-    issue1<0>(wbase, wlds); issue1<1>(wbase, wlds); issue1<2>(wbase, wlds); issue1<3>(wbase, wlds);
-    issue1<4>(wbase, wlds); issue1<5>(wbase, wlds); issue1<6>(wbase, wlds); issue1<7>(wbase, wlds);
+#pragma unroll
+    for (int q = 0; q < kDpw; q++) issue_q(q, wbase, wlds);
   }
 };
 
-template <bool RM> struct Frags {
+template <bool RM, int BK> struct Frags {
   // LDS byte offsets of this lane's fragment reads inside an operand tile.
-  //  r-contiguous: off[kk] for the 4 sub-slices; block a adds a*4096 (32 rows of 128 B).
+  //  r-contiguous: off[kk] for the sub-slices; block a adds a * 32 rows.
   //  r-major:      off[a] for the 4 blocks; sub-slice kk and half t add (kk*16 + 4t)*512.
   uint32_t off[4];
   __device__ __forceinline__ void init(int lane, int w /* wave coordinate along this operand */) {
@@ -124,11 +142,18 @@ template <bool RM> struct Frags {
         const int c = w * 16 + a * 4 + 2 * (G & 1) + ((p & 3) >> 1);
         off[a] = (uint32_t)(r * 512 + ((c ^ ((p >> 2) << 1)) * 16) + (p & 1) * 8);
       }
-    } else {
+    } else if (BK == 64) {
+      // rows of 128 B, chunk c of row r in slot c ^ (r & 7)
       const int row = w * 128 + (lane & 31);
       const int t0 = (lane >> 5) ^ (lane & 7);
 #pragma unroll
       for (int kk = 0; kk < 4; kk++) off[kk] = (uint32_t)(row * 128 + (((kk << 1) ^ t0) << 4));
+    } else {
+      // rows of 64 B, chunk c of row r in slot c ^ ((r >> 1) & 3): 8 consecutive rows cover all 32 banks
+      const int row = w * 128 + (lane & 31);
+      const int sw = (lane >> 1) & 3;
+#pragma unroll
+      for (int kk = 0; kk < 4; kk++) off[kk] = (uint32_t)(row * 64 + (((((kk & 1) << 1) | (lane >> 5)) ^ sw) << 4));
     }
   }
   __device__ __forceinline__ bf16x8 load(const lds_char* tile, int a, int kk) const {
@@ -142,203 +167,289 @@ template <bool RM> struct Frags {
       return __builtin_bit_cast(bf16x8, v);
     } else {
       typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
-      return *(const lds_bf16x8*)(tile + off[kk] + a * 4096);
+      return *(const lds_bf16x8*)(tile + off[kk] + a * (32 * BK * 2));
     }
   }
 };
 
-template <bool P_RM, bool Q_RM, int EPI>
+// Output tile of a logical tile index: bands of 8 output-row tiles, walked column-tile-major inside a band.
+struct TileCoord { int i0, j0; };
+__device__ __forceinline__ TileCoord tile_coord(int L, int tiles_i, int tiles_j) {
+  const int band_tiles = 8 * tiles_i;
+  const int band = L / band_tiles;
+  const int rem = L - band * band_tiles;
+  int band_h = tiles_j - band * 8;
+  if (band_h > 8) band_h = 8;
+  TileCoord c;
+  c.i0 = (rem / band_h) * kTile;
+  c.j0 = (band * 8 + rem % band_h) * kTile;
+  return c;
+}
+
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_bf16_kernel(FastParams p) {
+  typedef Geo<BK> G;
+  static_assert(NS * G::kStageBytes == kLdsStages, "stages must fill 128 KB");
+  static_assert((NS & (NS - 1)) == 0 && (G::kSub & 1) == 0, "power-of-two stages, even number of sub-slices");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const lds_char* lds = (const lds_char*)smem;
+  lds_char* lds = (lds_char*)smem;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wi = wave & 1, wj = wave >> 1;
 
-  // ---- workgroup -> tile: consecutive ids on one XCD (ids are dealt round-robin over the 8 XCDs) walk a band
-  // of 8 output-row tiles, so the 32 workgroups resident on an XCD share 4 P panels and 8 Q panels in its L2.
+  // ---- persistent workgroups: one per CU, each walks several output tiles.  Workgroup ids are dealt round-robin
+  // over the 8 XCDs, so XCD x owns the logical tiles [x T/8, (x+1) T/8) and its workgroups take them in turn: the 32
+  // workgroups resident on an XCD work on 32 consecutive logical tiles (4 column tiles x 8 row tiles of one band)
+  // and share 4 P panels and 8 Q panels in that XCD's L2.
   const int ntiles = p.tiles_i * p.tiles_j;
-  int L = blockIdx.x;
-  if ((ntiles & 7) == 0) L = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
-  const int band_tiles = 8 * p.tiles_i;
-  const int band = L / band_tiles;
-  const int rem = L - band * band_tiles;
-  int band_h = p.tiles_j - band * 8;
-  if (band_h > 8) band_h = 8;
-  const int ti = rem / band_h;
-  const int tj = band * 8 + rem % band_h;
-  const int i0 = ti * kTile, j0 = tj * kTile;
-  const int64_t r_begin = (int64_t)blockIdx.y * p.nkt * kBK;
-
-  Loader<P_RM> lp; lp.init(lane, p.ldp);
-  Loader<Q_RM> lq; lq.init(lane, p.ldq);
-  Frags<P_RM> fp; fp.init(lane, wi);
-  Frags<Q_RM> fq; fq.init(lane, wj);
-
-  const bf16_t* pbase = P_RM ? p.P + r_begin * p.ldp + i0 : p.P + (int64_t)i0 * p.ldp + r_begin;
-  const bf16_t* qbase = Q_RM ? p.Q + r_begin * p.ldq + j0 : p.Q + (int64_t)j0 * p.ldq + r_begin;
-  const int64_t pstep = P_RM ? (int64_t)kBK * p.ldp : kBK;
-  const int64_t qstep = Q_RM ? (int64_t)kBK * p.ldq : kBK;
-
-  f32x16 acc[4][4];
-#pragma unroll
-  for (int a = 0; a < 4; a++)
-#pragma unroll
-    for (int b = 0; b < 4; b++)
-#pragma unroll
-      for (int r = 0; r < 16; r++) acc[a][b][r] = 0.0f;
-
-  const int last = p.nkt - 1;
-  const uint32_t wlds = lds0 + (uint32_t)wave * 8192u;      // this wave's quarter of an operand tile
-  lp.issue(lp.wave_base(pbase, p.ldp, wave), wlds);
-  lq.issue(lq.wave_base(qbase, p.ldq, wave), wlds + kOperandBytes);
-  {
-    const int k1 = 1 < last ? 1 : last;
-    lp.issue(lp.wave_base(pbase + k1 * pstep, p.ldp, wave), wlds + kStageBytes);
-    lq.issue(lq.wave_base(qbase + k1 * qstep, p.ldq, wave), wlds + kStageBytes + kOperandBytes);
+  int L, Lstride, Lend;
+  if ((ntiles & 7) == 0 && (gridDim.x & 7) == 0) {
+    const int per_xcd = ntiles >> 3;
+    L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    Lstride = gridDim.x >> 3;
+    Lend = ((blockIdx.x & 7) + 1) * per_xcd;
+  } else {
+    L = blockIdx.x; Lstride = gridDim.x; Lend = ntiles;
   }
-  wait_dma();
+  const int64_t r_begin = (int64_t)blockIdx.y * p.nkt * BK;
+
+  Loader<P_RM, BK> lp; lp.init(lane, p.ldp);
+  Loader<Q_RM, BK> lq; lq.init(lane, p.ldq);
+  Frags<P_RM, BK> fp; fp.init(lane, wi);
+  Frags<Q_RM, BK> fq; fq.init(lane, wj);
+
+  const int64_t pstep = P_RM ? (int64_t)BK * p.ldp : BK;
+  const int64_t qstep = Q_RM ? (int64_t)BK * p.ldq : BK;
+  // first element this wave fetches of slice 0 of the tile at (i0, j0)
+  auto p_origin = [&](int i0) {
+    return lp.wave_base(P_RM ? p.P + r_begin * p.ldp + i0 : p.P + (int64_t)i0 * p.ldp + r_begin, p.ldp, wave);
+  };
+  auto q_origin = [&](int j0) {
+    return lq.wave_base(Q_RM ? p.Q + r_begin * p.ldq + j0 : p.Q + (int64_t)j0 * p.ldq + r_begin, p.ldq, wave);
+  };
+
+  const int nkt = p.nkt;                                                  // >= NS
+  const uint32_t wlds = lds0 + (uint32_t)wave * (uint32_t)G::kWaveBytes;  // this wave's quarter of an operand tile
+  TileCoord tc = tile_coord(L, p.tiles_i, p.tiles_j);
+  const bf16_t* pcur = p_origin(tc.i0);
+  const bf16_t* qcur = q_origin(tc.j0);
+#pragma unroll
+  for (int st = 0; st < NS; st++) {
+    lp.issue(pcur + st * pstep, wlds + st * G::kStageBytes);
+    lq.issue(qcur + st * qstep, wlds + st * G::kStageBytes + G::kOperandBytes);
+  }
+  wait_dma<0>();
   __syncthreads();
 
-  // Fragments are double-buffered in registers: while the 16 MFMAs of sub-slice kk run, the 8 fragment reads of
-  // sub-slice kk+1 are issued between them.  The last sub-slice's MFMAs are issued after the barrier that
+  // Fragments are double-buffered in registers: while the 16 MFMAs of a sub-slice run, the 8 fragment reads of the
+  // next sub-slice are issued between them.  The last sub-slice's MFMAs are issued after the barrier that
   // publishes the next stage, behind the first fragment reads of that stage, so the matrix pipe has work while
   // those reads are in flight.
   bf16x8 pf[2][4], qf[2][4];
 #pragma unroll
   for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds, a, 0);
 #pragma unroll
-  for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + kOperandBytes, b, 0);
+  for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + G::kOperandBytes, b, 0);
 
-  for (int kt = 0; kt < p.nkt; kt++) {
-    const int cur = kt & 1;
-    // Slice kt+2 is fetched into this slice's own stage as soon as the barrier below has shown that every wave
-    // holds its last fragments of slice kt in registers: the direct loads then have one whole slice time (the
-    // most two stages allow) before the next barrier needs them.  Slices past the end are clamped to the last
-    // one (fetched again, never read) so that the loop body is branch-free.
-    const int k2 = kt + 2 < last ? kt + 2 : last;
-    const uint32_t own = wlds + (uint32_t)cur * kStageBytes;
-    const bf16_t* pn = lp.wave_base(pbase + (int64_t)k2 * pstep, p.ldp, wave);
-    const bf16_t* qn = lq.wave_base(qbase + (int64_t)k2 * qstep, p.ldq, wave);
-    const lds_char* tp = lds + cur * kStageBytes;
-    const lds_char* tq = tp + kOperandBytes;
-    const lds_char* np_ = lds + (cur ^ 1) * kStageBytes;
-    const lds_char* nq_ = np_ + kOperandBytes;
-    // Issue order is pinned by hand (a scheduling barrier after every step): MFMA t of a sub-slice is followed by
-    // a fragment read of the next sub-slice (even t) and, in the last sub-slice, by one direct load, so neither
-    // the LDS reads nor the global loads keep the matrix pipe waiting for long.
-#pragma unroll
-    for (int kk = 0; kk < 4; kk++) {
-      const int use = kk & 1, fill = use ^ 1;
-      if (kk == 3) {
-        wait_dma();
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      const lds_char* rp = kk < 3 ? tp : np_;
-      const lds_char* rq = kk < 3 ? tq : nq_;
-      const int rk = kk < 3 ? kk + 1 : 0;
-#pragma unroll
-      for (int t = 0; t < 16; t++) {
-        const int a = t >> 2, b = t & 3;
-        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[use][a], qf[use][b], acc[a][b], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if ((t & 1) == 0) {
-          // read order: P0, Q0, Q1, Q2, Q3, P1, P2, P3 (the order in which the next sub-slice consumes them)
-          const int slot = t >> 1;
-          if (slot == 0) pf[fill][0] = fp.load(rp, 0, rk);
-          else if (slot <= 4) qf[fill][slot - 1] = fq.load(rq, slot - 1, rk);
-          else pf[fill][slot - 4] = fp.load(rp, slot - 4, rk);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        if (kk == 3) {
-          if (t < 8) lp.issue_q(t, pn, own);
-          else lq.issue_q(t - 8, qn, own + kOperandBytes);
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      }
-    }
-  }
-  wait_dma();   // the clamped re-fetches of the last two iterations must land before the workgroup may retire
-
-  // ------------------------------------------------------------------ epilogue
-  // accumulator register r of block (a, b): i = a*32 + (r/4)*8 + (lane/32)*4 + r%4, j = b*32 + lane%32
+  // epilogue constants.  Accumulator register r of block (a, b): i = a*32 + (r/4)*8 + (lane/32)*4 + r%4,
+  // j = b*32 + lane%32.  A lane's four adjacent values are only 8 bytes of an output row, so bf16 tiles leave
+  // through LDS: each wave owns 8 KB beyond the pipeline stages, writes one block row (32 output rows x 256 B) as
+  // [32 rows][32 units of 8 B] with unit u of row w in slot u ^ ((w & 15) << 1) (conflict-free both ways),
+  // reads it back 16 bytes per lane and stores 256 contiguous bytes per row.
   const int half = lane >> 5, l32 = lane & 31;
-  const int iw = i0 + wi * 128 + half * 4;     // + a*32 + g*8 + e
-  const int jw = j0 + wj * 128 + l32;          // + b*32
-  if (EPI == EPI_STORE) {
-    if (p.split > 1) {
-      float* out = p.Cpart + (int64_t)blockIdx.y * p.J * p.I;
+  lds_char* wtile = lds + kLdsStages + wave * 8192;
+  uint32_t woff[4][4];                         // LDS byte offset of the lane's 8-byte unit (a, g) in row l32
 #pragma unroll
-      for (int b = 0; b < 4; b++)
+  for (int a = 0; a < 4; a++)
 #pragma unroll
-        for (int a = 0; a < 4; a++)
-#pragma unroll
-          for (int g = 0; g < 4; g++) {
-            f32x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; e++) v[e] = acc[a][b][g * 4 + e];
-            *reinterpret_cast<f32x4*>(out + (int64_t)(jw + b * 32) * p.I + iw + a * 32 + g * 8) = v;
-          }
-    } else {
-#pragma unroll
-      for (int b = 0; b < 4; b++)
-#pragma unroll
-        for (int a = 0; a < 4; a++)
-#pragma unroll
-          for (int g = 0; g < 4; g++) {
-            bf16x4 v;
-#pragma unroll
-            for (int e = 0; e < 4; e++) v[e] = (bf16_t)acc[a][b][g * 4 + e];
-            *reinterpret_cast<bf16x4*>(p.C + (int64_t)(jw + b * 32) * p.I + iw + a * 32 + g * 8) = v;
-          }
-    }
-  } else {
-    // Z = acc + bias, rounded to bf16 and stored; A = GELU(stored Z); per output row j, mean and sum of squared
-    // deviations of A over this wave's 128 columns: 64 values in the lane, 64 in lane ^ 32.
-    f32x4 bias4[4][4];
+    for (int g = 0; g < 4; g++) woff[a][g] = (uint32_t)(l32 * 256 + (((a * 8 + g * 2) ^ ((l32 & 15) << 1)) + half) * 8);
+  typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+  int phase = 0;   // LDS stage that holds slice 0 of the current tile
+  for (;;) {
+    // the tile after this one (its first NS slices are fetched during this tile's last NS slices); a workgroup
+    // without a next tile fetches its own last slice again instead (never read)
+    const int Ln = L + Lstride;
+    const bool has_next = Ln < Lend;
+    const TileCoord tn = tile_coord(has_next ? Ln : L, p.tiles_i, p.tiles_j);
+    const bf16_t* pnext = p_origin(tn.i0);
+    const bf16_t* qnext = q_origin(tn.j0);
+
+    f32x16 acc[4][4];
 #pragma unroll
     for (int a = 0; a < 4; a++)
 #pragma unroll
-      for (int g = 0; g < 4; g++) bias4[a][g] = *reinterpret_cast<const f32x4*>(p.bias + iw + a * 32 + g * 8);
-    const int stat_tile = (i0 + wi * 128) >> 7;
+      for (int b = 0; b < 4; b++)
 #pragma unroll
-    for (int b = 0; b < 4; b++) {
-      const int64_t j = jw + b * 32;
-      float sum = 0.0f;
+        for (int r = 0; r < 16; r++) acc[a][b][r] = 0.0f;
+
+    for (int kt = 0; kt < nkt; kt++) {
+      const int cur = (kt + phase) & (NS - 1);
+      const int nxt = (cur + 1) & (NS - 1);
+      // Slice kt+NS is fetched into this slice's own stage as soon as the barrier below has shown that every wave
+      // holds its last fragments of slice kt in registers; those direct loads then have NS-1 slice times before
+      // the barrier that publishes them.
+      const int k2 = kt + NS;
+      const bool wraps = k2 >= nkt;
+      const int ks = wraps ? (has_next ? k2 - nkt : nkt - 1) : k2;
+      const bf16_t* pn = (wraps && has_next ? pnext : pcur) + (int64_t)ks * pstep;
+      const bf16_t* qn = (wraps && has_next ? qnext : qcur) + (int64_t)ks * qstep;
+      const uint32_t own = wlds + (uint32_t)cur * G::kStageBytes;
+      const lds_char* tp = lds + cur * G::kStageBytes;
+      const lds_char* tq = tp + G::kOperandBytes;
+      const lds_char* np_ = lds + nxt * G::kStageBytes;
+      const lds_char* nq_ = np_ + G::kOperandBytes;
+      // Issue order is pinned by hand (a scheduling barrier after every step): MFMA t of a sub-slice is followed
+      // by a fragment read of the next sub-slice (even t) and, in the last sub-slice, by a direct load, so
+      // neither the LDS reads nor the global loads keep the matrix pipe waiting for long.
 #pragma unroll
-      for (int a = 0; a < 4; a++)
+      for (int kk = 0; kk < G::kSub; kk++) {
+        const int use = kk & 1, fill = use ^ 1;
+        const bool lastsub = kk == G::kSub - 1;
+        if (lastsub) {
+          // slice kt+1 must have landed; the direct loads of the NS-2 slices after it may stay in flight
+          wait_dma<(NS - 2) * 2 * G::kDpw>();
+          __syncthreads();
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        const lds_char* rp = lastsub ? np_ : tp;
+        const lds_char* rq = lastsub ? nq_ : tq;
+        const int rk = lastsub ? 0 : kk + 1;
 #pragma unroll
-        for (int g = 0; g < 4; g++) {
-          bf16x4 zs;
-#pragma unroll
-          for (int e = 0; e < 4; e++) {
-            zs[e] = (bf16_t)(acc[a][b][g * 4 + e] + bias4[a][g][e]);
-            const float act = gelu<float>((float)zs[e]);
-            acc[a][b][g * 4 + e] = act;
-            sum += act;
+        for (int t = 0; t < 16; t++) {
+          const int a = t >> 2, b = t & 3;
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[use][a], qf[use][b], acc[a][b], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if ((t & 1) == 0) {
+            // read order: P0, Q0, Q1, Q2, Q3, P1, P2, P3 (the order in which the next sub-slice consumes them)
+            const int slot = t >> 1;
+            if (slot == 0) pf[fill][0] = fp.load(rp, 0, rk);
+            else if (slot <= 4) qf[fill][slot - 1] = fq.load(rq, slot - 1, rk);
+            else pf[fill][slot - 4] = fp.load(rp, slot - 4, rk);
+            __builtin_amdgcn_sched_barrier(0);
           }
-          *reinterpret_cast<bf16x4*>(p.C + j * p.I + iw + a * 32 + g * 8) = zs;
+          if (lastsub) {
+            if (G::kDpw == 8) {            // 16 direct loads: one behind every MFMA
+              if (t < 8) lp.issue_q(t, pn, own);
+              else lq.issue_q(t - 8, qn, own + G::kOperandBytes);
+              __builtin_amdgcn_sched_barrier(0);
+            } else if (t & 1) {            // 8 direct loads: one behind every other MFMA
+              const int d = t >> 1;
+              if (d < 4) lp.issue_q(d, pn, own);
+              else lq.issue_q(d - 4, qn, own + G::kOperandBytes);
+              __builtin_amdgcn_sched_barrier(0);
+            }
+          }
         }
-      sum += __shfl_xor(sum, 32, kWave);
-      const float mean = sum * (1.0f / 128.0f);
-      float m2 = 0.0f;
-#pragma unroll
-      for (int a = 0; a < 4; a++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const float d = acc[a][b][r] - mean;
-          m2 = __builtin_fmaf(d, d, m2);
-        }
-      m2 += __shfl_xor(m2, 32, kWave);
-      if (half == 0) {
-        f32x2 o; o[0] = mean; o[1] = m2;
-        p.part[(int64_t)stat_tile * p.J + j] = o;
       }
     }
+    phase = (phase + nkt) & (NS - 1);
+    // here: the next tile's slice 0 has landed in stage `phase`, its following slices are in flight
+
+    // ---------------------------------------------------------------- epilogue of tile (tc.i0, tc.j0)
+    const int i0 = tc.i0, j0 = tc.j0;
+    const int iw = i0 + wi * 128 + half * 4;     // + a*32 + g*8 + e
+    const int jw = j0 + wj * 128 + l32;          // + b*32
+    // Block row b of the wave tile (32 output rows) leaves as soon as it is complete, so the reads and stores of
+    // one block row overlap the arithmetic of the next.
+    auto flush_rows = [&](int b) {
+      // rows it*4 + lane/16 of the block row, 16-byte chunk lane%16 (slot chunk ^ (row & 15))
+      const int m = lane & 15, rq = lane >> 4;
+      bf16_t* crow = p.C + (int64_t)(j0 + wj * 128 + b * 32 + rq) * p.I + i0 + wi * 128 + m * 8;
+#pragma unroll
+      for (int it = 0; it < 8; it++) {
+        const int w = it * 4 + rq;
+        const u32x4 v = *(const lds_u32x4*)(wtile + w * 256 + ((m ^ (((it & 3) * 4 + rq) & 15)) << 4));
+        *reinterpret_cast<u32x4*>(crow + (int64_t)(it * 4) * p.I) = v;
+      }
+    };
+    if (EPI == EPI_STORE) {
+      if (p.split > 1) {
+        float* out = p.Cpart + (int64_t)blockIdx.y * p.J * p.I;
+#pragma unroll
+        for (int b = 0; b < 4; b++)
+#pragma unroll
+          for (int a = 0; a < 4; a++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+              f32x4 v;
+#pragma unroll
+              for (int e = 0; e < 4; e++) v[e] = acc[a][b][g * 4 + e];
+              *reinterpret_cast<f32x4*>(out + (int64_t)(jw + b * 32) * p.I + iw + a * 32 + g * 8) = v;
+            }
+      } else {
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+#pragma unroll
+          for (int a = 0; a < 4; a++)
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+              bf16x4 v;
+#pragma unroll
+              for (int e = 0; e < 4; e++) v[e] = (bf16_t)acc[a][b][g * 4 + e];
+              *(lds_bf16x4*)(wtile + woff[a][g]) = v;
+            }
+          flush_rows(b);
+        }
+      }
+    } else {
+      // Z = acc + bias, rounded to bf16 and stored; A = GELU(stored Z); per output row j, mean and sum of squared
+      // deviations of A over this wave's 128 columns: 64 values in the lane, 64 in lane ^ 32.
+      f32x4 bias4[4][4];
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int g = 0; g < 4; g++) bias4[a][g] = *reinterpret_cast<const f32x4*>(p.bias + iw + a * 32 + g * 8);
+      const int stat_tile = (i0 + wi * 128) >> 7;
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        const int64_t j = jw + b * 32;
+        float sum = 0.0f;
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+          for (int g = 0; g < 4; g++) {
+            bf16x4 zs;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              zs[e] = (bf16_t)(acc[a][b][g * 4 + e] + bias4[a][g][e]);
+              const float act = gelu<float>((float)zs[e]);
+              acc[a][b][g * 4 + e] = act;
+              sum += act;
+            }
+            *(lds_bf16x4*)(wtile + woff[a][g]) = zs;
+          }
+        sum += __shfl_xor(sum, 32, kWave);
+        const float mean = sum * (1.0f / 128.0f);
+        float m2 = 0.0f;
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const float d = acc[a][b][r] - mean;
+            m2 = __builtin_fmaf(d, d, m2);
+          }
+        m2 += __shfl_xor(m2, 32, kWave);
+        if (half == 0) {
+          f32x2 o; o[0] = mean; o[1] = m2;
+          p.part[(int64_t)stat_tile * p.J + j] = o;
+        }
+        flush_rows(b);
+      }
+    }
+
+    if (!has_next) break;
+    L = Ln; tc = tn; pcur = pnext; qcur = qnext;
+    // first fragments of the next tile (its slice 0 landed before the last barrier above); reading them here
+    // rather than carrying them through the epilogue keeps 64 registers free there
+#pragma unroll
+    for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds + phase * G::kStageBytes, a, 0);
+#pragma unroll
+    for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + phase * G::kStageBytes + G::kOperandBytes, b, 0);
   }
+  wait_dma<0>();   // the re-fetches issued during the last tile must land before the workgroup may retire
 }
 
 // Sum split-reduction partials [split][n] fp32 -> bf16.
@@ -356,27 +467,47 @@ __global__ __launch_bounds__(256) void reduce_split_kernel(const float* __restri
   *reinterpret_cast<bf16x4*>(out + i) = o;
 }
 
-template <bool P_RM, bool Q_RM, int EPI> void launch(const FastParams& p, hipStream_t s) {
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS> void launch(const FastParams& p, hipStream_t s) {
   static bool configured = false;   // raise the dynamic LDS limit once per kernel
-  auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI>;
+  auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI, BK, NS>;
   if (!configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     configured = true;
   }
-  const dim3 grid((unsigned)(p.tiles_i * p.tiles_j), (unsigned)p.split);
+  // persistent: at most one workgroup per CU (the LDS footprint allows no more); a multiple of 8 whenever the
+  // tile count is, so that every XCD gets the same number
+  const int ntiles = p.tiles_i * p.tiles_j;
+  int wgs = 256 / p.split;
+  if (wgs < 8) wgs = 8;
+  if (wgs > ntiles) wgs = ntiles;
+  if ((ntiles & 7) == 0) wgs &= ~7;
+  const dim3 grid((unsigned)wgs, (unsigned)p.split);
   hipLaunchKernelGGL(kern, grid, dim3(256), kLdsBytes, s, p);
 }
 
-bool dims_ok(int64_t I, int64_t J, int64_t R) {
-  return I > 0 && J > 0 && R > 0 && I % kTile == 0 && J % kTile == 0 && R % kBK == 0 &&
+// Pipeline shape per contraction (slice width, stages): 64 x 2 or 32 x 4, both 128 KB of LDS.
+#ifndef FDL_F1_BK
+#define FDL_F1_BK 64
+#endif
+#ifndef FDL_B3_BK
+#define FDL_B3_BK 32
+#endif
+#ifndef FDL_B4_BK
+#define FDL_B4_BK 32
+#endif
+constexpr int kF1BK = FDL_F1_BK, kB3BK = FDL_B3_BK, kB4BK = FDL_B4_BK;
+constexpr int stages_of(int bk) { return kLdsStages / (2 * kTile * bk * 2); }
+
+bool dims_ok(int64_t I, int64_t J, int64_t R, int bk) {
+  return I > 0 && J > 0 && R > 0 && I % kTile == 0 && J % kTile == 0 && R % bk == 0 && R >= stages_of(bk) * bk &&
          I <= (1 << 24) && J <= (1 << 24) && (I / kTile) * (J / kTile) <= (1 << 30);
 }
 
 }  // namespace
 
-bool fast_f1_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(N, M, K); }
-bool fast_b3_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, M, N); }
-bool fast_b4_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, N, M); }
+bool fast_f1_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(N, M, K, kF1BK); }
+bool fast_b3_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, M, N, kB3BK); }
+bool fast_b4_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, N, M, kB4BK); }
 int fast_f1_stat_tile_w() { return 128; }
 
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
@@ -385,8 +516,8 @@ void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* 
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)X; p.ldp = K; p.ldq = K;
   p.C = (bf16_t*)Zsave; p.bias = bias; p.part = (f32x2*)part;
   p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)(M / kTile);
-  p.nkt = (int)(K / kBK); p.split = 1;
-  launch<false, false, EPI_F1>(p, s);
+  p.nkt = (int)(K / kF1BK); p.split = 1;
+  launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
 }
 
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s) {
@@ -394,14 +525,14 @@ void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void*
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = N;
   p.C = (bf16_t*)dX;
   p.I = (int)K; p.J = (int)M; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)(M / kTile);
-  p.nkt = (int)(N / kBK); p.split = 1;
-  launch<true, false, EPI_STORE>(p, s);
+  p.nkt = (int)(N / kB3BK); p.split = 1;
+  launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK)>(p, s);
 }
 
-// Split of the reduction over M so that small dW outputs still fill the chip: each part keeps >= 8 slices.
+// Split of the reduction over M so that small dW outputs still fill the chip: each part keeps >= 512 rows.
 int fast_b4_split(int64_t M, int64_t K, int64_t N) {
   const int64_t tiles = (K / kTile) * (N / kTile);
-  const int64_t slices = M / kBK;
+  const int64_t slices = M / 64;
   int split = 1;
   while (tiles * split * 2 <= 256 && slices % (split * 2) == 0 && slices / (split * 2) >= 8) split *= 2;
   return split;
@@ -413,8 +544,8 @@ void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, const void* dZ, 
   p.P = (const bf16_t*)X; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = N;
   p.C = (bf16_t*)dW; p.Cpart = (float*)dwpart;
   p.I = (int)K; p.J = (int)N; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)(N / kTile);
-  p.nkt = (int)(M / kBK / split); p.split = split;
-  launch<true, true, EPI_STORE>(p, s);
+  p.nkt = (int)(M / kB4BK / split); p.split = split;
+  launch<true, true, EPI_STORE, kB4BK, stages_of(kB4BK)>(p, s);
   if (split > 1) {
     const int64_t n = N * K;
     hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s,

@@ -88,3 +88,12 @@ def test_backward_rejects_bad_arguments_before_any_launch():
     assert _bwd(ws=P + 128) == api.FDL_ERR_ALIGN
     assert _bwd(dW=P + 4) == api.FDL_ERR_ALIGN
     assert _bwd(dbeta=P + 1) == api.FDL_ERR_ALIGN
+
+
+def test_one_hip_runtime_in_the_process():
+    """torch ships its own HIP runtime; the library must bind to that copy, whatever the import order of the
+    test modules, or launches on torch buffers fail with device errors."""
+    loaded = {ln.split()[-1] for ln in open("/proc/self/maps") if "libamdhip64" in ln}
+    assert len(loaded) == 1, loaded
+    import torch
+    assert os.path.dirname(torch.__file__) in next(iter(loaded))
