@@ -56,20 +56,24 @@ template <> struct Gauss<double> {
 template <> struct Gauss<float> {
   static __device__ __forceinline__ float cdf(float z) {
     const float zc = __builtin_amdgcn_fmed3f(z, -4.0f, 4.0f);
-    const float zs = zc * 0.25f;
-    const float u = zs * zs;
-    float p = 3.463215330e-01f;
-    p = __builtin_fmaf(p, u, -1.879980461e+00f);
-    p = __builtin_fmaf(p, u, 4.556957157e+00f);
-    p = __builtin_fmaf(p, u, -6.600788584e+00f);
-    p = __builtin_fmaf(p, u, 6.482041631e+00f);
-    p = __builtin_fmaf(p, u, -4.644545581e+00f);
-    p = __builtin_fmaf(p, u, 2.528634197e+00f);
-    p = __builtin_fmaf(p, u, -1.062569532e+00f);
+    // P is fitted in (zc/4)^2; its coefficients are scaled by exact powers of two so that Horner runs on zc^2
+    const float u = zc * zc;
+    float p = 3.463215330e-01f * 0x1p-32f;
+    p = __builtin_fmaf(p, u, -1.879980461e+00f * 0x1p-28f);
+    p = __builtin_fmaf(p, u, 4.556957157e+00f * 0x1p-24f);
+    p = __builtin_fmaf(p, u, -6.600788584e+00f * 0x1p-20f);
+    p = __builtin_fmaf(p, u, 6.482041631e+00f * 0x1p-16f);
+    p = __builtin_fmaf(p, u, -4.644545581e+00f * 0x1p-12f);
+    p = __builtin_fmaf(p, u, 2.528634197e+00f * 0x1p-8f);
+    p = __builtin_fmaf(p, u, -1.062569532e+00f * 0x1p-4f);
     p = __builtin_fmaf(p, u, 3.989227098e-01f);
     return __builtin_fmaf(zc, p, 0.5f);
   }
-  static __device__ __forceinline__ float gelu_of(float z, float Phi) { return __builtin_fmaxf(z, -4.0f) * Phi; }
+  // max(z, -4) written as the median of (z, -4, largest finite float): one instruction, where a plain maximum
+  // first canonicalises its input (the two agree for every finite z)
+  static __device__ __forceinline__ float gelu_of(float z, float Phi) {
+    return __builtin_amdgcn_fmed3f(z, -4.0f, 3.402823466e+38f) * Phi;
+  }
   static __device__ __forceinline__ void eval(float z, float& Phi, float& phi) {
     Phi = cdf(z);
     phi = __builtin_amdgcn_exp2f(-0.72134752044448170368f * z * z) * 0.39894228040143267794f;   // exp(-z^2/2)/sqrt(2 pi)

@@ -44,6 +44,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   // ---- forward
   q.f1_fast = dt == kBF16 && fast_f1_supported(M, K, N);
   auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  q.f2_rows = q.f1_fast && f2_rows_supported(dt, N);
   q.f1_wb = pick_wb(Mp, N);
   q.stat_tile_w = q.f1_fast ? fast_f1_stat_tile_w() : 16 * q.f1_wb;
   q.stat_tiles = (int)((N + q.stat_tile_w - 1) / q.stat_tile_w);
@@ -171,7 +172,7 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
   {
     PhaseTimer t(FDL_PHASE_F1, s);
     if (p.f1_fast) {
-      launch_fast_f1(M, K, N, X, W, b, Zsave, part, s);
+      launch_fast_f1(M, K, N, X, W, b, Zsave, p.f2_rows ? nullptr : part, s);
     } else {
       GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
       launch_generic_f1((int)dt, g, b, Zsave, part, s);
@@ -179,11 +180,12 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
   }
   {
     PhaseTimer t(FDL_PHASE_FS, s);
-    launch_stats_finalize(part, p.stat_tiles, p.stat_tile_w, M, N, eps, mean, rstd, s);
+    if (!p.f2_rows) launch_stats_finalize(part, p.stat_tiles, p.stat_tile_w, M, N, eps, mean, rstd, s);
   }
   {
     PhaseTimer t(FDL_PHASE_F2, s);
-    launch_f2((int)dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+    if (p.f2_rows) launch_f2_rows(M, N, eps, Zsave, gamma, beta, Y, mean, rstd, s);
+    else launch_f2((int)dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
   }
   return launch_status();
 }

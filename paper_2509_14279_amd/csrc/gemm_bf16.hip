@@ -45,14 +45,14 @@ template <int BK> struct Geo {
   static constexpr int kWaveBytes = kOperandBytes / 4;    // each wave fills a quarter of an operand tile
 };
 
-enum { EPI_STORE = 0, EPI_F1 = 1 };
+enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2 };
 
 struct FastParams {
   const bf16_t* P; const bf16_t* Q;
   int64_t ldp, ldq;
   bf16_t* C;             // [J][I]
   float* Cpart;          // [split][J][I] fp32 (split > 1)
-  const float* bias;     // [I]   (EPI_F1)
+  const float* bias;     // [I]   (EPI_F1, EPI_BIAS)
   f32x2* part;           // [I/128][J]  (EPI_F1)
   int I, J;
   int tiles_i, tiles_j;
@@ -362,7 +362,10 @@ void gemm_bf16_kernel(FastParams p) {
       for (int it = 0; it < 8; it++) {
         const int w = it * 4 + rq;
         const u32x4 v = *(const lds_u32x4*)(wtile + w * 256 + ((m ^ (((it & 3) * 4 + rq) & 15)) << 4));
-        *reinterpret_cast<u32x4*>(crow + (int64_t)(it * 4) * p.I) = v;
+        // the forward output (Zsave, far larger than the caches) is streamed past them so that it does not evict
+        // the operand panels the XCD's workgroups share; the smaller gradient outputs gain nothing from that
+        if (EPI == EPI_STORE) *reinterpret_cast<u32x4*>(crow + (int64_t)(it * 4) * p.I) = v;
+        else __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(crow + (int64_t)(it * 4) * p.I));
       }
     };
     if (EPI == EPI_STORE) {
@@ -393,6 +396,22 @@ void gemm_bf16_kernel(FastParams p) {
             }
           flush_rows(b);
         }
+      }
+    } else if (EPI == EPI_BIAS) {
+      // Z = acc + bias, rounded to bf16 and stored (the row statistics are taken by the normalisation kernel)
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+          for (int g = 0; g < 4; g++) {
+            const f32x4 bias4 = *reinterpret_cast<const f32x4*>(p.bias + iw + a * 32 + g * 8);
+            bf16x4 zs;
+#pragma unroll
+            for (int e = 0; e < 4; e++) zs[e] = (bf16_t)(acc[a][b][g * 4 + e] + bias4[e]);
+            *(lds_bf16x4*)(wtile + woff[a][g]) = zs;
+          }
+        flush_rows(b);
       }
     } else {
       // Z = acc + bias, rounded to bf16 and stored; A = GELU(stored Z); per output row j, mean and sum of squared
@@ -510,6 +529,7 @@ bool fast_b3_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, M, N
 bool fast_b4_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, N, M, kB4BK); }
 int fast_f1_stat_tile_w() { return 128; }
 
+// part != nullptr: also emit the per-(row, 128-column tile) partial statistics of GELU(Zsave)
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
                     void* part, hipStream_t s) {
   FastParams p = {};
@@ -517,7 +537,8 @@ void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* 
   p.C = (bf16_t*)Zsave; p.bias = bias; p.part = (f32x2*)part;
   p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)(M / kTile);
   p.nkt = (int)(K / kF1BK); p.split = 1;
-  launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
+  if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
+  else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK)>(p, s);
 }
 
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s) {

@@ -4,6 +4,8 @@
 // Phases:  F1  Z = X W^T + b, Zsave, per-(row, column tile) partial statistics of GELU(Zsave)
 //          FS  merge partial statistics -> mean, rstd
 //          F2  Y = (GELU(Zsave) - mean) rstd gamma + beta
+//              (bf16 fast path with rows that fit a wavefront's registers: F1 stores Zsave only, F2 takes the
+//               statistics itself and FS is empty)
 //          B1  dZ and the column partials of dbeta, dgamma, db  (B1a: row sums c1, c2 first)
 //          B2  column partials -> dbeta, dgamma, db
 //          B3  dX = dZ W            B4  dW = dZ^T X
@@ -21,6 +23,7 @@ struct Plan {
   int64_t M, K, N;
   // forward
   int f1_fast;            // 1: bf16 fast MFMA kernel, 0: generic kernel
+  int f2_rows;            // 1: F1 stores Zsave only; one kernel takes the row statistics and normalises (no FS)
   int f1_wb;              // generic kernel: 16x16 blocks per wave tile side (wave tile = 16*wb)
   int stat_tile_w;        // width of one partial-statistics column tile
   int stat_tiles;         // number of such tiles per row
@@ -64,6 +67,10 @@ void launch_stats_finalize(const void* part, int tiles, int tile_w, int64_t M, i
                            float* mean, float* rstd, hipStream_t s);
 void launch_f2(int dt, int64_t M, int64_t N, const void* Zsave, const float* mean, const float* rstd,
                const float* gamma, const float* beta, void* Y, hipStream_t s);
+// statistics and normalisation in one kernel (a wavefront per row); replaces FS + F2 when F1 emits no partials
+bool f2_rows_supported(int dt, int64_t N);
+void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const float* gamma, const float* beta, void* Y,
+                    float* mean, float* rstd, hipStream_t s);
 void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave, const float* gamma,
                 const float* mean, const float* rstd, void* c12, hipStream_t s);
 void launch_b1b(int dt, int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Zsave,

@@ -69,6 +69,126 @@ __global__ __launch_bounds__(256) void f2_kernel(int64_t M, int64_t N, int rows_
 }
 
 // ------------------------------------------------------------------------------------------------
+// F2 with its own statistics (bf16 storage, N % 8 == 0, N <= 512 CH): a wavefront owns a row and keeps it in
+// registers over three sweeps (GELU and sum; deviations and their squares; scale, shift, store), so Zsave is read
+// once, no partial statistics pass through memory and no barrier separates the sweeps.  Lane l holds the 8-element
+// vectors c*64 + l, c < CH, of its row (every load and store of a wavefront covers 1 KB of one row); the next
+// row's vectors are fetched while the current row is processed.  gamma and beta sit in LDS, permuted so that a
+// lane's four 16-byte reads per vector are lane-contiguous.  Workgroups of NT/64 wavefronts walk the rows with
+// stride (8 wavefronts; 4 for the widest masked variant, whose extra per-vector state needs the larger register
+// budget of one wavefront per SIMD).
+// FULL: N == 512 CH, every lane holds every vector.  Otherwise the vectors past the end of the row are fetched
+// from a clamped address, masked to zero (GELU(0) = 0 adds nothing to the sum), left out of the squared
+// deviations and never stored; the code stays free of divergent branches either way.
+template <int CH, bool FULL, int NT>
+__global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float eps, const bf16_t* __restrict__ Z,
+                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                      bf16_t* __restrict__ Y, float* __restrict__ mean,
+                                                      float* __restrict__ rstd) {
+  // products are formed once and reused (fusing GELU's final multiplication into each later use would keep
+  // both of its factors alive for every element of the row); the fused operations wanted are written out
+#pragma clang fp contract(off)
+  extern __shared__ f32x4 gb[];   // [CH][4][64]: gamma[0:4], gamma[4:8], beta[0:4], beta[4:8] of vector c*64 + lane
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: row addresses stay scalar
+  const int nvec = (int)(N >> 3);
+  for (int idx = threadIdx.x; idx < CH * 64; idx += NT) {
+    const int64_t src = (int64_t)(idx < nvec ? idx : nvec - 1) * 8;
+    const int c = idx >> 6, l = idx & 63;
+    gb[(c * 4 + 0) * 64 + l] = *reinterpret_cast<const f32x4*>(gamma + src);
+    gb[(c * 4 + 1) * 64 + l] = *reinterpret_cast<const f32x4*>(gamma + src + 4);
+    gb[(c * 4 + 2) * 64 + l] = *reinterpret_cast<const f32x4*>(beta + src);
+    gb[(c * 4 + 3) * 64 + l] = *reinterpret_cast<const f32x4*>(beta + src + 4);
+  }
+  __syncthreads();
+  const int64_t nw = (int64_t)gridDim.x * (NT / 64);
+  const float inv_n = 1.0f / (float)N;
+  // per-lane element offset of vector c inside a row, and whether the row has that vector
+  int voff[CH];
+  uint32_t keep[CH];
+#pragma unroll
+  for (int c = 0; c < CH; c++) {
+    const int vi = c * 64 + lane;
+    voff[c] = (FULL || vi < nvec ? vi : nvec - 1) * 8;
+    keep[c] = (FULL || vi < nvec) ? 0xffffffffu : 0u;
+  }
+
+  u32x4 raw[CH];
+  auto fetch = [&](int64_t r) {
+    const bf16_t* zr = Z + (r < M ? r : M - 1) * N;   // past the last row: a harmless re-read, never used
+#pragma unroll
+    for (int c = 0; c < CH; c++) {
+      if (FULL) {
+        // scalar base per vector + one shared per-lane offset (the immediate offset field reaches only 4 KB)
+        const bf16_t* zc = zr + c * 512;
+        asm("" : "+s"(zc));
+        raw[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(zc + lane * 8));
+      } else {
+        raw[c] = *reinterpret_cast<const u32x4*>(zr + voff[c]);
+      }
+    }
+  };
+  int64_t row = (int64_t)blockIdx.x * (NT / 64) + wave;
+  fetch(row);
+  for (; row < M; row += nw) {
+    float a[CH][8];
+    float sum = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; c++) {
+#pragma unroll
+      for (int h = 0; h < 4; h++) {
+        const uint32_t w = FULL ? raw[c][h] : (raw[c][h] & keep[c]);
+        a[c][2 * h] = gelu<float>(__builtin_bit_cast(float, w << 16));              // bf16 -> fp32 is a 16-bit shift
+        a[c][2 * h + 1] = gelu<float>(__builtin_bit_cast(float, w & 0xffff0000u));
+        sum += a[c][2 * h];
+        sum += a[c][2 * h + 1];
+      }
+      // eight polynomial evaluations side by side are enough to cover the arithmetic latency; interleaving all
+      // of a row's would keep three temporaries per element alive
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // the next row is requested only once this row has been unpacked, so that a row of packed values and a row
+    // of fp32 values are all a lane ever holds
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(row + nw);
+    __builtin_amdgcn_sched_barrier(0);
+    const float mu = wave_sum(sum) * inv_n;
+    float m2 = 0.0f;
+#pragma unroll
+    for (int c = 0; c < CH; c++)
+#pragma unroll
+      for (int v = 0; v < 8; v++) {
+        const float d = a[c][v] - mu;
+        a[c][v] = FULL ? d : (keep[c] ? d : 0.0f);
+        m2 = __builtin_fmaf(a[c][v], a[c][v], m2);
+      }
+    const float rs = 1.0f / __builtin_sqrtf(wave_sum(m2) * inv_n + eps);
+    if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+    bf16_t* yr = Y + row * N;
+#pragma unroll
+    for (int c = 0; c < CH; c++) {
+      const f32x4 g0 = gb[(c * 4 + 0) * 64 + lane], g1 = gb[(c * 4 + 1) * 64 + lane];
+      const f32x4 b0 = gb[(c * 4 + 2) * 64 + lane], b1 = gb[(c * 4 + 3) * 64 + lane];
+      bf16x8 o;
+#pragma unroll
+      for (int v = 0; v < 4; v++) {
+        o[v] = (bf16_t)__builtin_fmaf(a[c][v] * rs, g0[v], b0[v]);
+        o[v + 4] = (bf16_t)__builtin_fmaf(a[c][v + 4] * rs, g1[v], b1[v]);
+      }
+      if (FULL) {
+        bf16_t* yc = yr + c * 512;
+        asm("" : "+s"(yc));
+        __builtin_nontemporal_store(o, reinterpret_cast<bf16x8*>(yc + lane * 8));
+      } else if (keep[c]) {
+        *reinterpret_cast<bf16x8*>(yr + voff[c]) = o;
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads of later vectors from being hoisted (registers)
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
 // sum of two values over a workgroup of NW wavefronts; `red` is this call's LDS slot ([NW][2] of C)
 template <class C, int NW> __device__ __forceinline__ void wg_sum2(C& a, C& b, C (*red)[2]) {
   a = wave_sum(a);
@@ -167,8 +287,10 @@ template <> struct RawVec<float, 1> { typedef float type; };
 template <> struct RawVec<bf16_t, 8> { typedef bf16x8 type; };
 template <> struct RawVec<bf16_t, 1> { typedef bf16_t type; };
 
+// Row data is used once per pass and is far larger than the caches: loads and stores of the big row-major
+// tensors carry the non-temporal hint.
 template <class T, int V> __device__ __forceinline__ typename RawVec<T, V>::type raw_load(const T* p) {
-  return *reinterpret_cast<const typename RawVec<T, V>::type*>(p);
+  return __builtin_nontemporal_load(reinterpret_cast<const typename RawVec<T, V>::type*>(p));
 }
 template <class T, int V, class C> __device__ __forceinline__ C raw_get(const typename RawVec<T, V>::type& r, int v) {
   if constexpr (V == 1) return (C)to_f32<T>(r); else return (C)to_f32<T>(r[v]);
@@ -251,7 +373,11 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
         dz[v] = (g[s][v] - c1 - ah[s][v] * c2) * gp[s][v];
         accz[s][v] += dz[v];
       }
-      if (ok[s]) VecIO<T, V>::store(dZ + row * N + col[s], dz);
+      if (ok[s]) {
+        typename RawVec<T, V>::type o;
+        if constexpr (V == 1) o = to_storage<T, C>(dz[0]); else { for (int v = 0; v < V; v++) o[v] = to_storage<T, C>(dz[v]); }
+        __builtin_nontemporal_store(o, reinterpret_cast<typename RawVec<T, V>::type*>(dZ + row * N + col[s]));
+      }
     }
   };
   for (int64_t row = blockIdx.x; row < M; row += 2 * G) {
@@ -390,6 +516,32 @@ void launch_f2(int dt, int64_t M, int64_t N, const void* Zsave, const float* mea
                const float* gamma, const float* beta, void* Y, hipStream_t s) {
   if (dt == kF32) f2_impl<float>(M, N, Zsave, mean, rstd, gamma, beta, Y, s);
   else f2_impl<bf16_t>(M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+}
+
+bool f2_rows_supported(int dt, int64_t N) { return dt == kBF16 && N % 8 == 0 && N <= 8192; }
+
+void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const float* gamma, const float* beta, void* Y,
+                    float* mean, float* rstd, hipStream_t s) {
+  int ch = 2;
+  while (ch * 512 < N) ch *= 2;
+  const bool full = N == (int64_t)ch * 512;
+  const int nt = (!full && ch == 16) ? 256 : 512;
+  // a workgroup of the widest variant fills a CU's register file; narrower rows leave room for more of them
+  const int64_t per_wg = nt / 64;
+  int64_t wgs = (M + per_wg - 1) / per_wg;
+  const int64_t cap = 256 * (16 / ch);
+  if (wgs > cap) wgs = cap;
+#define FDL_F2R(CHH, FULL, NTT)                                                                                    \
+  hipLaunchKernelGGL((f2_rows_kernel<CHH, FULL, NTT>), dim3((unsigned)wgs), dim3(NTT), (size_t)CHH * 4096, s, M, N,   \
+                     eps, (const bf16_t*)Zsave, gamma, beta, (bf16_t*)Y, mean, rstd)
+  if (full) {
+    if (ch == 2) FDL_F2R(2, true, 512); else if (ch == 4) FDL_F2R(4, true, 512);
+    else if (ch == 8) FDL_F2R(8, true, 512); else FDL_F2R(16, true, 512);
+  } else {
+    if (ch == 2) FDL_F2R(2, false, 512); else if (ch == 4) FDL_F2R(4, false, 512);
+    else if (ch == 8) FDL_F2R(8, false, 512); else FDL_F2R(16, false, 256);
+  }
+#undef FDL_F2R
 }
 
 void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave, const float* gamma, const float* mean,

@@ -91,6 +91,10 @@ def test_small_and_ragged_shapes(dtype, shape):
     ("f32", (384, 128, 1024)), ("f32", (100, 64, 4100)),      # f32 rows longer than the fused row kernel holds
     ("bf16", (24, 16, 8200)), ("bf16", (16, 8, 2051)),        # bf16 rows beyond the fused kernel (aligned / unaligned)
     ("f32", (8, 8, 2051)),
+    # bf16 fast path, row lengths on both sides of what the wavefront-per-row normalisation holds (8192) and of its
+    # vector counts (exact fits 2048 / 8192; masked tails 4352 / 7936; 8448 takes the in-GEMM statistics instead)
+    ("bf16", (256, 64, 2048)), ("bf16", (512, 64, 8192)), ("bf16", (256, 64, 4352)), ("bf16", (256, 64, 7936)),
+    ("bf16", (256, 128, 8448)),
 ])
 def test_aligned_and_long_row_shapes(dtype, shape):
     M, K, N = shape
@@ -109,6 +113,16 @@ def test_constant_rows_and_zero_weight(dtype):
     t["b"].fill_(0.5)                      # constant row: variance 0, eps keeps rstd finite, Y = beta
     got, ref = full_compare(cfg, t, f32_atol=DEGENERATE_F32_ATOL)
     np.testing.assert_allclose(H.to_f64(got["Y"]), np.broadcast_to(t["beta"].numpy(), (40, 72)), atol=1e-2 if dtype == "bf16" else DEGENERATE_F32_ATOL)
+
+
+def test_constant_rows_fast_path():
+    """Same degenerate case at a shape the bf16 MFMA fast path and the wavefront-per-row normalisation take."""
+    cfg = I.custom("bf16", 256, 64, 1024, seed=9)
+    t = I.generate(cfg)
+    t["W"].zero_()
+    t["b"].fill_(0.5)
+    got, ref = full_compare(cfg, t)
+    np.testing.assert_allclose(H.to_f64(got["Y"]), np.broadcast_to(t["beta"].numpy(), (256, 1024)), atol=1e-2)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
