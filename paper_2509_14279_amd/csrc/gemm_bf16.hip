@@ -45,7 +45,7 @@ template <int BK> struct Geo {
   static constexpr int kWaveBytes = kOperandBytes / 4;    // each wave fills a quarter of an operand tile
 };
 
-enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2 };
+enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2, EPI_PARTIAL = 3 };
 
 struct FastParams {
   const bf16_t* P; const bf16_t* Q;
@@ -72,6 +72,12 @@ typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 template <int LDS_OFF>
 __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_base) {
   asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(sbase), "s"(lds_base), "n"(LDS_OFF) : "memory", "m0", "scc");
+}
+// 4 bytes per lane: lane l's dword lands at (lds_base + LDS_OFF) + 4 l
+template <int LDS_OFF>
+__device__ __forceinline__ void dma4(uint32_t voff, const void* sbase, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
                :: "v"(voff), "s"(sbase), "s"(lds_base), "n"(LDS_OFF) : "memory", "m0", "scc");
 }
 // wait until at most N vector-memory operations of this wave are outstanding (loads complete in order)
@@ -215,10 +221,19 @@ void gemm_bf16_kernel(FastParams p) {
   }
   const int64_t r_begin = (int64_t)blockIdx.y * p.nkt * BK;
 
-  Loader<P_RM, BK> lp; lp.init(lane, p.ldp);
-  Loader<Q_RM, BK> lq; lq.init(lane, p.ldq);
-  Frags<P_RM, BK> fp; fp.init(lane, wi);
-  Frags<Q_RM, BK> fq; fq.init(lane, wj);
+  // Per-lane offsets of the direct loads and of the fragment reads.  They are recomputed at the top of every tile
+  // (from a copy of the lane id the compiler cannot see through) rather than kept across the epilogue, where the
+  // register allocator would otherwise park them in scratch memory: a reload there has to wait for every output
+  // store issued before it, because vector memory operations retire in order.
+  Loader<P_RM, BK> lp; Loader<Q_RM, BK> lq;
+  Frags<P_RM, BK> fp; Frags<Q_RM, BK> fq;
+  auto init_offsets = [&]() {
+    int lt = lane;
+    asm volatile("" : "+v"(lt));
+    lp.init(lt, p.ldp); lq.init(lt, p.ldq);
+    fp.init(lt, wi); fq.init(lt, wj);
+  };
+  init_offsets();   // for the initial fill below; every tile recomputes them
 
   const int64_t pstep = P_RM ? (int64_t)BK * p.ldp : BK;
   const int64_t qstep = Q_RM ? (int64_t)BK * p.ldq : BK;
@@ -248,27 +263,29 @@ void gemm_bf16_kernel(FastParams p) {
   // publishes the next stage, behind the first fragment reads of that stage, so the matrix pipe has work while
   // those reads are in flight.
   bf16x8 pf[2][4], qf[2][4];
-#pragma unroll
-  for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds, a, 0);
-#pragma unroll
-  for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + G::kOperandBytes, b, 0);
 
-  // epilogue constants.  Accumulator register r of block (a, b): i = a*32 + (r/4)*8 + (lane/32)*4 + r%4,
-  // j = b*32 + lane%32.  A lane's four adjacent values are only 8 bytes of an output row, so bf16 tiles leave
-  // through LDS: each wave owns 8 KB beyond the pipeline stages, writes one block row (32 output rows x 256 B) as
-  // [32 rows][32 units of 8 B] with unit u of row w in slot u ^ ((w & 15) << 1) (conflict-free both ways),
-  // reads it back 16 bytes per lane and stores 256 contiguous bytes per row.
   const int half = lane >> 5, l32 = lane & 31;
-  lds_char* wtile = lds + kLdsStages + wave * 8192;
-  uint32_t woff[4][4];                         // LDS byte offset of the lane's 8-byte unit (a, g) in row l32
-#pragma unroll
-  for (int a = 0; a < 4; a++)
-#pragma unroll
-    for (int g = 0; g < 4; g++) woff[a][g] = (uint32_t)(l32 * 256 + (((a * 8 + g * 2) ^ ((l32 & 15) << 1)) + half) * 8);
   typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
+  // Forward: the bias enters through the matrix pipe as one extra reduction step after the last slice,
+  // acc += Pb Qb^T with Pb[i][0..2] = the three bf16 pieces of bias[i] (hi + mid + lo = the fp32 value exactly:
+  // 3 x 8 significant bits) and Qb[j][0..2] = 1: sixteen MFMAs per tile and no vector arithmetic in the epilogue.
+  // A lane needs the bias of one column per block a (only lanes 0..31 carry k = 0..7).  The wave's 128 bias
+  // values are fetched at the top of the tile by two direct loads into its output staging area, which is idle
+  // until the epilogue: like every direct load they are older than the slice loads issued after them, so the main
+  // loop's own waits cover them, and no register or compiler-inserted wait is involved.
+  constexpr bool kBias = EPI == EPI_BIAS || EPI == EPI_F1;
 
   int phase = 0;   // LDS stage that holds slice 0 of the current tile
   for (;;) {
+    // slice 0 of this tile has landed in stage `phase` (initial fill, or prefetched during the previous tile and
+    // published by its last barrier): first fragments
+    init_offsets();
+#pragma unroll
+    for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds + phase * G::kStageBytes, a, 0);
+#pragma unroll
+    for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + phase * G::kStageBytes + G::kOperandBytes, b, 0);
+
     // the tile after this one (its first NS slices are fetched during this tile's last NS slices); a workgroup
     // without a next tile fetches its own last slice again instead (never read)
     const int Ln = L + Lstride;
@@ -276,6 +293,15 @@ void gemm_bf16_kernel(FastParams p) {
     const TileCoord tn = tile_coord(has_next ? Ln : L, p.tiles_i, p.tiles_j);
     const bf16_t* pnext = p_origin(tn.i0);
     const bf16_t* qnext = q_origin(tn.j0);
+
+    if (kBias) {
+      int lb = lane;
+      asm volatile("" : "+v"(lb));
+      const float* bsrc = p.bias + tc.i0 + wi * 128;
+      const uint32_t wst = lds0 + (uint32_t)kLdsStages + (uint32_t)wave * 8192u;
+      dma4<0>((uint32_t)lb * 4u, bsrc, wst);
+      dma4<256>((uint32_t)lb * 4u, bsrc + 64, wst);
+    }
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -349,78 +375,114 @@ void gemm_bf16_kernel(FastParams p) {
     // here: the next tile's slice 0 has landed in stage `phase`, its following slices are in flight
 
     // ---------------------------------------------------------------- epilogue of tile (tc.i0, tc.j0)
+    // Accumulator register r of block (a, b): i = a*32 + (r/4)*8 + (lane/32)*4 + r%4, j = b*32 + lane%32.  A lane's
+    // four adjacent values are only 8 bytes of an output row, so bf16 tiles leave through LDS: each wave owns 8 KB
+    // beyond the pipeline stages, writes one block row (32 output rows x 256 B) as [32 rows][32 units of 8 B] with
+    // unit u of row w in slot u ^ ((w & 15) << 1) (conflict-free both ways), reads it back 16 bytes per lane and
+    // stores 256 contiguous bytes per row.
+    // Every per-lane constant of the epilogue is derived here from a copy of the lane id the compiler cannot see
+    // through: hoisted out of the tile loop they would be spilled around the main loop, and each reload in the
+    // epilogue would wait for the output stores issued before it (vector memory operations retire in order).
+    if (kBias) {
+      bf16x8 ones, bfrag[4];
+#pragma unroll
+      for (int e = 0; e < 8; e++) ones[e] = (bf16_t)(e < 3 ? 1.0f : 0.0f);
+#pragma unroll
+      for (int a = 0; a < 4; a++) {
+        typedef __attribute__((address_space(3))) float lds_float;
+        const float xb = *(const lds_float*)(lds + kLdsStages + wave * 8192 + (a * 32 + l32) * 4);
+        const float x = half == 0 ? xb : 0.0f;
+        const bf16_t hi = (bf16_t)x;
+        const float r1 = x - (float)hi;
+        const bf16_t mid = (bf16_t)r1;
+        const bf16_t lo = (bf16_t)(r1 - (float)mid);
+#pragma unroll
+        for (int e = 0; e < 8; e++) bfrag[a][e] = (bf16_t)0.0f;
+        bfrag[a][0] = hi; bfrag[a][1] = mid; bfrag[a][2] = lo;
+      }
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[a], ones, acc[a][b], 0, 0, 0);
+    }
+    if (!kBias) {
+      // give the register allocator a fresh start for the accumulators here, as the bias MFMAs do in the forward
+      // kernels (without it, it parks a few of them in scratch memory across the epilogue)
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) asm volatile("" : "+a"(acc[a][b]));
+    }
+    int le = lane;
+    asm volatile("" : "+v"(le));
+    const int e_half = le >> 5, e_l32 = le & 31;
     const int i0 = tc.i0, j0 = tc.j0;
-    const int iw = i0 + wi * 128 + half * 4;     // + a*32 + g*8 + e
-    const int jw = j0 + wj * 128 + l32;          // + b*32
-    // Block row b of the wave tile (32 output rows) leaves as soon as it is complete, so the reads and stores of
-    // one block row overlap the arithmetic of the next.
+    const int jw = j0 + wj * 128 + e_l32;          // + b*32
+    lds_char* wtile = lds + kLdsStages + wave * 8192;
+    uint32_t woff[4][4];                         // LDS byte offset of the lane's 8-byte unit (a, g) in row lane%32
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int g = 0; g < 4; g++)
+        woff[a][g] = (uint32_t)(e_l32 * 256 + (((a * 8 + g * 2) ^ ((e_l32 & 15) << 1)) + e_half) * 8);
+    // read side: rows it*4 + lane/16 of the block row, 16-byte chunk lane%16 (slot chunk ^ (row & 15))
+    const int e_m = le & 15, e_rq = le >> 4;
+    uint32_t roff[4];
+#pragma unroll
+    for (int c = 0; c < 4; c++) roff[c] = (uint32_t)((c * 4 + e_rq) * 256 + ((e_m ^ (c * 4 + e_rq)) << 4));
+    const uint32_t svoff = (uint32_t)(e_rq * p.I + e_m * 8) * 2u;   // byte offset of the lane inside 4 output rows
+    // Block row b of the wave tile (32 output rows) leaves as soon as it is complete.
     auto flush_rows = [&](int b) {
-      // rows it*4 + lane/16 of the block row, 16-byte chunk lane%16 (slot chunk ^ (row & 15))
-      const int m = lane & 15, rq = lane >> 4;
-      bf16_t* crow = p.C + (int64_t)(j0 + wj * 128 + b * 32 + rq) * p.I + i0 + wi * 128 + m * 8;
+      // wave-uniform base of row it*4 of the block row; the lane adds (lane/16) rows and 16 (lane%16) bytes
+      char* cbase = reinterpret_cast<char*>(p.C + (int64_t)(j0 + wj * 128 + b * 32) * p.I + i0 + wi * 128);
 #pragma unroll
       for (int it = 0; it < 8; it++) {
-        const int w = it * 4 + rq;
-        const u32x4 v = *(const lds_u32x4*)(wtile + w * 256 + ((m ^ (((it & 3) * 4 + rq) & 15)) << 4));
+        const u32x4 v = *(const lds_u32x4*)(wtile + roff[it & 3] + (it >> 2) * 4096);
+        u32x4* dst = reinterpret_cast<u32x4*>(cbase + (int64_t)(it * 4) * p.I * 2 + svoff);
         // the forward output (Zsave, far larger than the caches) is streamed past them so that it does not evict
         // the operand panels the XCD's workgroups share; the smaller gradient outputs gain nothing from that
-        if (EPI == EPI_STORE) *reinterpret_cast<u32x4*>(crow + (int64_t)(it * 4) * p.I) = v;
-        else __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(crow + (int64_t)(it * 4) * p.I));
+        if (kBias) __builtin_nontemporal_store(v, dst);
+        else *dst = v;
       }
     };
-    if (EPI == EPI_STORE) {
-      if (p.split > 1) {
-        float* out = p.Cpart + (int64_t)blockIdx.y * p.J * p.I;
+    if (EPI == EPI_PARTIAL) {
+      // fp32 partial sums of this reduction part, straight from the registers (wave-uniform base + lane offset)
+      float* out = p.Cpart + (int64_t)blockIdx.y * p.J * p.I;
+      const uint32_t pvoff = (uint32_t)(e_l32 * p.I + e_half * 4) * 4u;
 #pragma unroll
-        for (int b = 0; b < 4; b++)
+      for (int b = 0; b < 4; b++) {
+        char* obase = reinterpret_cast<char*>(out + (int64_t)(j0 + wj * 128 + b * 32) * p.I + i0 + wi * 128);
 #pragma unroll
-          for (int a = 0; a < 4; a++)
+        for (int a = 0; a < 4; a++)
 #pragma unroll
-            for (int g = 0; g < 4; g++) {
-              f32x4 v;
+          for (int g = 0; g < 4; g++) {
+            f32x4 v;
 #pragma unroll
-              for (int e = 0; e < 4; e++) v[e] = acc[a][b][g * 4 + e];
-              *reinterpret_cast<f32x4*>(out + (int64_t)(jw + b * 32) * p.I + iw + a * 32 + g * 8) = v;
-            }
-      } else {
-#pragma unroll
-        for (int b = 0; b < 4; b++) {
-#pragma unroll
-          for (int a = 0; a < 4; a++)
-#pragma unroll
-            for (int g = 0; g < 4; g++) {
-              bf16x4 v;
-#pragma unroll
-              for (int e = 0; e < 4; e++) v[e] = (bf16_t)acc[a][b][g * 4 + e];
-              *(lds_bf16x4*)(wtile + woff[a][g]) = v;
-            }
-          flush_rows(b);
-        }
+            for (int e = 0; e < 4; e++) v[e] = acc[a][b][g * 4 + e];
+            *reinterpret_cast<f32x4*>(obase + (a * 32 + g * 8) * 4 + pvoff) = v;
+          }
+        __builtin_amdgcn_sched_barrier(0);
       }
-    } else if (EPI == EPI_BIAS) {
-      // Z = acc + bias, rounded to bf16 and stored (the row statistics are taken by the normalisation kernel)
+    } else if (EPI != EPI_F1) {
+      // rounded to bf16 and stored (forward: the bias is in the accumulators since their start; the row statistics
+      // are taken by the normalisation kernel)
 #pragma unroll
       for (int b = 0; b < 4; b++) {
 #pragma unroll
         for (int a = 0; a < 4; a++)
 #pragma unroll
           for (int g = 0; g < 4; g++) {
-            const f32x4 bias4 = *reinterpret_cast<const f32x4*>(p.bias + iw + a * 32 + g * 8);
-            bf16x4 zs;
+            bf16x4 v;
 #pragma unroll
-            for (int e = 0; e < 4; e++) zs[e] = (bf16_t)(acc[a][b][g * 4 + e] + bias4[e]);
-            *(lds_bf16x4*)(wtile + woff[a][g]) = zs;
+            for (int e = 0; e < 4; e++) v[e] = (bf16_t)acc[a][b][g * 4 + e];
+            *(lds_bf16x4*)(wtile + woff[a][g]) = v;
           }
         flush_rows(b);
+        __builtin_amdgcn_sched_barrier(0);   // one block row at a time: keeps the accumulator copies in few registers
       }
     } else {
-      // Z = acc + bias, rounded to bf16 and stored; A = GELU(stored Z); per output row j, mean and sum of squared
+      // Z (bias included) rounded to bf16 and stored; A = GELU(stored Z); per output row j, mean and sum of squared
       // deviations of A over this wave's 128 columns: 64 values in the lane, 64 in lane ^ 32.
-      f32x4 bias4[4][4];
-#pragma unroll
-      for (int a = 0; a < 4; a++)
-#pragma unroll
-        for (int g = 0; g < 4; g++) bias4[a][g] = *reinterpret_cast<const f32x4*>(p.bias + iw + a * 32 + g * 8);
       const int stat_tile = (i0 + wi * 128) >> 7;
 #pragma unroll
       for (int b = 0; b < 4; b++) {
@@ -433,7 +495,7 @@ void gemm_bf16_kernel(FastParams p) {
             bf16x4 zs;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
-              zs[e] = (bf16_t)(acc[a][b][g * 4 + e] + bias4[a][g][e]);
+              zs[e] = (bf16_t)acc[a][b][g * 4 + e];
               const float act = gelu<float>((float)zs[e]);
               acc[a][b][g * 4 + e] = act;
               sum += act;
@@ -451,22 +513,17 @@ void gemm_bf16_kernel(FastParams p) {
             m2 = __builtin_fmaf(d, d, m2);
           }
         m2 += __shfl_xor(m2, 32, kWave);
-        if (half == 0) {
+        if (e_half == 0) {
           f32x2 o; o[0] = mean; o[1] = m2;
           p.part[(int64_t)stat_tile * p.J + j] = o;
         }
         flush_rows(b);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
 
     if (!has_next) break;
     L = Ln; tc = tn; pcur = pnext; qcur = qnext;
-    // first fragments of the next tile (its slice 0 landed before the last barrier above); reading them here
-    // rather than carrying them through the epilogue keeps 64 registers free there
-#pragma unroll
-    for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds + phase * G::kStageBytes, a, 0);
-#pragma unroll
-    for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + phase * G::kStageBytes + G::kOperandBytes, b, 0);
   }
   wait_dma<0>();   // the re-fetches issued during the last tile must land before the workgroup may retire
 }
@@ -566,7 +623,8 @@ void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, const void* dZ, 
   p.C = (bf16_t*)dW; p.Cpart = (float*)dwpart;
   p.I = (int)K; p.J = (int)N; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)(N / kTile);
   p.nkt = (int)(M / kB4BK / split); p.split = split;
-  launch<true, true, EPI_STORE, kB4BK, stages_of(kB4BK)>(p, s);
+  if (split > 1) launch<true, true, EPI_PARTIAL, kB4BK, stages_of(kB4BK)>(p, s);
+  else launch<true, true, EPI_STORE, kB4BK, stages_of(kB4BK)>(p, s);
   if (split > 1) {
     const int64_t n = N * K;
     hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s,
