@@ -29,6 +29,8 @@
 #include "common.hip.h"
 #include "internal.h"
 
+#include <type_traits>
+
 namespace fdl {
 namespace {
 
@@ -303,15 +305,16 @@ void gemm_bf16_kernel(FastParams p) {
       dma4<256>((uint32_t)lb * 4u, bsrc + 64, wst);
     }
 
+    // The accumulators are never cleared: the first sub-slice of a tile's slice 0 runs its MFMAs with a zero
+    // addend (slice 0 has its own copy of the slice code for that; the other slices, at least NS-1 of them -
+    // checked on the host - run in the loop).
     f32x16 acc[4][4];
+    f32x16 zero16;
 #pragma unroll
-    for (int a = 0; a < 4; a++)
-#pragma unroll
-      for (int b = 0; b < 4; b++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) acc[a][b][r] = 0.0f;
+    for (int r = 0; r < 16; r++) zero16[r] = 0.0f;
 
-    for (int kt = 0; kt < nkt; kt++) {
+    auto slice = [&](const int kt, auto first_tag) {
+      constexpr bool kFirst = decltype(first_tag)::value;
       const int cur = (kt + phase) & (NS - 1);
       const int nxt = (cur + 1) & (NS - 1);
       // Slice kt+NS is fetched into this slice's own stage as soon as the barrier below has shown that every wave
@@ -346,7 +349,10 @@ void gemm_bf16_kernel(FastParams p) {
 #pragma unroll
         for (int t = 0; t < 16; t++) {
           const int a = t >> 2, b = t & 3;
-          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[use][a], qf[use][b], acc[a][b], 0, 0, 0);
+          if (kFirst && kk == 0)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[use][a], qf[use][b], zero16, 0, 0, 0);
+          else
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[use][a], qf[use][b], acc[a][b], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
           if ((t & 1) == 0) {
             // read order: P0, Q0, Q1, Q2, Q3, P1, P2, P3 (the order in which the next sub-slice consumes them)
@@ -370,6 +376,11 @@ void gemm_bf16_kernel(FastParams p) {
           }
         }
       }
+    };
+    slice(0, std::true_type());
+    {
+      int kt = 1;
+      do { slice(kt, std::false_type()); } while (++kt < nkt);
     }
     phase = (phase + nkt) & (NS - 1);
     // here: the next tile's slice 0 has landed in stage `phase`, its following slices are in flight
