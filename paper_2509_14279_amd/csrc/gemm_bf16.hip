@@ -257,6 +257,10 @@ void gemm_bf16_kernel(FastParams p) {
     lp.issue(pcur + st * pstep, wlds + st * G::kStageBytes);
     lq.issue(qcur + st * qstep, wlds + st * G::kStageBytes + G::kOperandBytes);
   }
+  // the slice fetched last, as (addresses, index inside its tile)
+  const bf16_t* pfetch = pcur + (NS - 1) * pstep;
+  const bf16_t* qfetch = qcur + (NS - 1) * qstep;
+  int fidx = NS - 1;
   wait_dma<0>();
   __syncthreads();
 
@@ -293,8 +297,10 @@ void gemm_bf16_kernel(FastParams p) {
     const int Ln = L + Lstride;
     const bool has_next = Ln < Lend;
     const TileCoord tn = tile_coord(has_next ? Ln : L, p.tiles_i, p.tiles_j);
-    const bf16_t* pnext = p_origin(tn.i0);
-    const bf16_t* qnext = q_origin(tn.j0);
+    // where the fetch stream continues after this tile's last slice
+    const bf16_t* pwrap = has_next ? p_origin(tn.i0) : p_origin(tc.i0) + (int64_t)(nkt - 1) * pstep;
+    const bf16_t* qwrap = has_next ? q_origin(tn.j0) : q_origin(tc.j0) + (int64_t)(nkt - 1) * qstep;
+    const int fwrap = has_next ? 0 : nkt - 1;
 
     if (kBias) {
       int lb = lane;
@@ -319,12 +325,9 @@ void gemm_bf16_kernel(FastParams p) {
       const int nxt = (cur + 1) & (NS - 1);
       // Slice kt+NS is fetched into this slice's own stage as soon as the barrier below has shown that every wave
       // holds its last fragments of slice kt in registers; those direct loads then have NS-1 slice times before
-      // the barrier that publishes them.
-      const int k2 = kt + NS;
-      const bool wraps = k2 >= nkt;
-      const int ks = wraps ? (has_next ? k2 - nkt : nkt - 1) : k2;
-      const bf16_t* pn = (wraps && has_next ? pnext : pcur) + (int64_t)ks * pstep;
-      const bf16_t* qn = (wraps && has_next ? qnext : qcur) + (int64_t)ks * qstep;
+      // the barrier that publishes them.  (pfetch, qfetch, fidx) name the slice fetched last and are stepped in
+      // the shadow of the last sub-slice's first MFMA: a handful of scalar instructions, where recomputing the
+      // addresses from the slice index cost two dozen in front of every slice's first MFMA.
       const uint32_t own = wlds + (uint32_t)cur * G::kStageBytes;
       const lds_char* tp = lds + cur * G::kStageBytes;
       const lds_char* tq = tp + G::kOperandBytes;
@@ -354,6 +357,23 @@ void gemm_bf16_kernel(FastParams p) {
           else
             acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pf[use][a], qf[use][b], acc[a][b], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
+          // next slice of the fetch stream: the following one of this tile, else (pwrap, qwrap, fwrap) = slice 0
+          // of the next tile or, without a next tile, this tile's last slice again, which is never read; spread
+          // over three MFMA shadows
+          if (lastsub && t == 0) {
+            pfetch = fidx + 1 == nkt ? pwrap : pfetch + pstep;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (lastsub && t == 2) {
+            qfetch = fidx + 1 == nkt ? qwrap : qfetch + qstep;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (lastsub && t == 4) {
+            fidx = fidx + 1 == nkt ? fwrap : fidx + 1;
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          const bf16_t* const pn = pfetch;
+          const bf16_t* const qn = qfetch;
           if ((t & 1) == 0) {
             // read order: P0, Q0, Q1, Q2, Q3, P1, P2, P3 (the order in which the next sub-slice consumes them)
             const int slot = t >> 1;
@@ -534,7 +554,7 @@ void gemm_bf16_kernel(FastParams p) {
     }
 
     if (!has_next) break;
-    L = Ln; tc = tn; pcur = pnext; qcur = qnext;
+    L = Ln; tc = tn;
   }
   wait_dma<0>();   // the re-fetches issued during the last tile must land before the workgroup may retire
 }
