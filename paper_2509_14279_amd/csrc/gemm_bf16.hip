@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_bf16_kernel(FastParams p) {
   typedef Geo<BK> G;
   static_assert(NS * G::kStageBytes == kLdsStages, "stages must fill 128 KB");
-  static_assert((NS & (NS - 1)) == 0 && (G::kSub & 1) == 0, "power-of-two stages, even number of sub-slices");
+  static_assert((NS == 2 || NS == 4) && (G::kSub & 1) == 0, "2 or 4 stages, even number of sub-slices");
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   lds_char* lds = (lds_char*)smem;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
@@ -282,15 +282,14 @@ void gemm_bf16_kernel(FastParams p) {
   // loop's own waits cover them, and no register or compiler-inserted wait is involved.
   constexpr bool kBias = EPI == EPI_BIAS || EPI == EPI_F1;
 
-  int phase = 0;   // LDS stage that holds slice 0 of the current tile
   for (;;) {
-    // slice 0 of this tile has landed in stage `phase` (initial fill, or prefetched during the previous tile and
+    // slice 0 of this tile has landed in stage 0 (initial fill, or prefetched during the previous tile and
     // published by its last barrier): first fragments
     init_offsets();
 #pragma unroll
-    for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds + phase * G::kStageBytes, a, 0);
+    for (int a = 0; a < 4; a++) pf[0][a] = fp.load(lds, a, 0);
 #pragma unroll
-    for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + phase * G::kStageBytes + G::kOperandBytes, b, 0);
+    for (int b = 0; b < 4; b++) qf[0][b] = fq.load(lds + G::kOperandBytes, b, 0);
 
     // the tile after this one (its first NS slices are fetched during this tile's last NS slices); a workgroup
     // without a next tile fetches its own last slice again instead (never read)
@@ -319,10 +318,13 @@ void gemm_bf16_kernel(FastParams p) {
 #pragma unroll
     for (int r = 0; r < 16; r++) zero16[r] = 0.0f;
 
-    auto slice = [&](const int kt, auto first_tag) {
+    // One slice; the LDS stage it lives in is a compile-time constant (the number of slices per tile is a multiple
+    // of NS - checked on the host - so a tile's slice 0 is always in stage 0 and the slice loop is unrolled NS
+    // times): every LDS address is then a per-lane register plus an immediate.
+    auto slice = [&](auto stage_tag, auto first_tag) {
       constexpr bool kFirst = decltype(first_tag)::value;
-      const int cur = (kt + phase) & (NS - 1);
-      const int nxt = (cur + 1) & (NS - 1);
+      constexpr int cur = decltype(stage_tag)::value;
+      constexpr int nxt = (cur + 1) & (NS - 1);
       // Slice kt+NS is fetched into this slice's own stage as soon as the barrier below has shown that every wave
       // holds its last fragments of slice kt in registers; those direct loads then have NS-1 slice times before
       // the barrier that publishes them.  (pfetch, qfetch, fidx) name the slice fetched last and are stepped in
@@ -397,13 +399,17 @@ void gemm_bf16_kernel(FastParams p) {
         }
       }
     };
-    slice(0, std::true_type());
-    {
-      int kt = 1;
-      do { slice(kt, std::false_type()); } while (++kt < nkt);
-    }
-    phase = (phase + nkt) & (NS - 1);
-    // here: the next tile's slice 0 has landed in stage `phase`, its following slices are in flight
+    auto group = [&](auto first_tag) {
+      slice(std::integral_constant<int, 0>(), first_tag);
+      slice(std::integral_constant<int, 1>(), std::false_type());
+      if constexpr (NS == 4) {
+        slice(std::integral_constant<int, 2>(), std::false_type());
+        slice(std::integral_constant<int, 3>(), std::false_type());
+      }
+    };
+    group(std::true_type());
+    for (int g = NS; g < nkt; g += NS) group(std::false_type());
+    // here: the next tile's slice 0 has landed in stage 0, its following slices are in flight
 
     // ---------------------------------------------------------------- epilogue of tile (tc.i0, tc.j0)
     // Accumulator register r of block (a, b): i = a*32 + (r/4)*8 + (lane/32)*4 + r%4, j = b*32 + lane%32.  A lane's
@@ -606,7 +612,7 @@ constexpr int kF1BK = FDL_F1_BK, kB3BK = FDL_B3_BK, kB4BK = FDL_B4_BK;
 constexpr int stages_of(int bk) { return kLdsStages / (2 * kTile * bk * 2); }
 
 bool dims_ok(int64_t I, int64_t J, int64_t R, int bk) {
-  return I > 0 && J > 0 && R > 0 && I % kTile == 0 && J % kTile == 0 && R % bk == 0 && R >= stages_of(bk) * bk &&
+  return I > 0 && J > 0 && R > 0 && I % kTile == 0 && J % kTile == 0 && R % (stages_of(bk) * bk) == 0 &&
          I <= (1 << 24) && J <= (1 << 24) && (I / kTile) * (J / kTile) <= (1 << 30);
 }
 
@@ -641,9 +647,9 @@ void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void*
 // Split of the reduction over M so that small dW outputs still fill the chip: each part keeps >= 512 rows.
 int fast_b4_split(int64_t M, int64_t K, int64_t N) {
   const int64_t tiles = (K / kTile) * (N / kTile);
-  const int64_t slices = M / 64;
+  const int64_t unit = (int64_t)kB4BK * stages_of(kB4BK);   // every part is a whole number of slice groups
   int split = 1;
-  while (tiles * split * 2 <= 256 && slices % (split * 2) == 0 && slices / (split * 2) >= 8) split *= 2;
+  while (tiles * split * 2 <= 256 && M % (split * 2 * unit) == 0 && M / (split * 2) >= 512) split *= 2;
   return split;
 }
 

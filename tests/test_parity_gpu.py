@@ -93,8 +93,10 @@ def test_small_and_ragged_shapes(dtype, shape):
     ("f32", (8, 8, 2051)),
     # bf16 fast path, row lengths on both sides of what the wavefront-per-row normalisation holds (8192) and of its
     # vector counts (exact fits 2048 / 8192; masked tails 4352 / 7936; 8448 takes the in-GEMM statistics instead)
-    ("bf16", (256, 64, 2048)), ("bf16", (512, 64, 8192)), ("bf16", (256, 64, 4352)), ("bf16", (256, 64, 7936)),
+    ("bf16", (256, 128, 2048)), ("bf16", (512, 128, 8192)), ("bf16", (256, 128, 4352)), ("bf16", (256, 128, 7936)),
     ("bf16", (256, 128, 8448)),
+    # reduction lengths that are not a whole number of pipeline rounds fall back to the generic GEMM per contraction
+    ("bf16", (256, 64, 512)), ("bf16", (320, 192, 256)),
 ])
 def test_aligned_and_long_row_shapes(dtype, shape):
     M, K, N = shape
@@ -117,7 +119,7 @@ def test_constant_rows_and_zero_weight(dtype):
 
 def test_constant_rows_fast_path():
     """Same degenerate case at a shape the bf16 MFMA fast path and the wavefront-per-row normalisation take."""
-    cfg = I.custom("bf16", 256, 64, 1024, seed=9)
+    cfg = I.custom("bf16", 256, 128, 1024, seed=9)
     t = I.generate(cfg)
     t["W"].zero_()
     t["b"].fill_(0.5)
