@@ -125,4 +125,24 @@ template <class C> __device__ __forceinline__ C wave_sum(C v) {
   return v;
 }
 
+// fp32: data-parallel-primitive lane moves folded into the adds instead of LDS permutes.
+// dpp_f<CTRL, ROW_MASK>(x): the value of the lane CTRL selects; lanes in rows outside ROW_MASK read 0.
+template <int CTRL, int ROW_MASK> __device__ __forceinline__ float dpp_f(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, ROW_MASK, 0xF, false));
+}
+// sum inside each row of 16 lanes; every lane of a row receives its row's sum
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_f<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]: lane ^ 1
+  v += dpp_f<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]: lane ^ 2
+  v += dpp_f<0x141, 0xF>(v);   // row_half_mirror: the other quad of each 8
+  v += dpp_f<0x140, 0xF>(v);   // row_mirror: the other half of the row
+  return v;
+}
+template <> __device__ __forceinline__ float wave_sum<float>(float v) {
+  v = row16_sum(v);
+  v += dpp_f<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3: rows 0+1, rows 2+3
+  v += dpp_f<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3: row 3 now holds the total
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+
 }  // namespace fdl

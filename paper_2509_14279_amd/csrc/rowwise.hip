@@ -196,10 +196,19 @@ template <class C, int NW> __device__ __forceinline__ void wg_sum2(C& a, C& b, C
   const int wave = threadIdx.x >> 6;
   if ((threadIdx.x & 63) == 0) { red[wave][0] = a; red[wave][1] = b; }
   __syncthreads();
-  a = red[0][0];
-  b = red[0][1];
+  if constexpr (sizeof(C) == 4 && NW <= 16) {
+    // lane w of every row of 16 lanes takes wavefront w's pair; one row sum finishes both totals
+    const int l = threadIdx.x & 15;
+    a = l < NW ? red[l < NW ? l : 0][0] : (C)0;
+    b = l < NW ? red[l < NW ? l : 0][1] : (C)0;
+    a = row16_sum(a);
+    b = row16_sum(b);
+  } else {
+    a = red[0][0];
+    b = red[0][1];
 #pragma unroll
-  for (int w = 1; w < NW; w++) { a += red[w][0]; b += red[w][1]; }
+    for (int w = 1; w < NW; w++) { a += red[w][0]; b += red[w][1]; }
+  }
 }
 
 // B1a (two-kernel path): c1_i = mean_j g_ij, c2_i = mean_j g_ij Ahat_ij with g = dY gamma.
