@@ -351,8 +351,10 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
   fetch(0, blockIdx.x);
   fetch(1, blockIdx.x + G);
 
+  const C inv_n = (C)1 / (C)N;
   auto process = [&](int buf, int64_t row) {
     const C mu = (C)mean[row], rs = (C)rstd[row];
+    const C nmr = -mu * rs;
     C ah[S][V], gp[S][V], g[S][V];
     C s1 = 0, s2 = 0;
 #pragma unroll
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
         const C dy = raw_get<T, V, C>(bdy[buf][s], v);
         C Phi, phi;
         Gauss<C>::eval(z, Phi, phi);
-        ah[s][v] = (Gauss<C>::gelu_of(z, Phi) - mu) * rs;
+        ah[s][v] = Gauss<C>::gelu_of(z, Phi) * rs + nmr;   // (A - mean) rstd, one fused multiply-add
         gp[s][v] = (Phi + z * phi) * rs;
         g[s][v] = dy * gm[s][v];
         s1 += g[s][v];
@@ -373,7 +375,7 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
       }
     fetch(buf, row + 2 * G);
     wg_sum2<C, NT / 64>(s1, s2, red[buf]);
-    const C c1 = s1 / (C)N, c2 = s2 / (C)N;
+    const C c1 = s1 * inv_n, c2 = s2 * inv_n;
 #pragma unroll
     for (int s = 0; s < S; s++) {
       C dz[V];
