@@ -148,6 +148,65 @@ def torch_eager_ms(cfg, dev_t, iters=5):
     return (time.perf_counter() - t0) * 1e3 / iters
 
 
+# Shapes for --sweep: the seeded configurations the kernels were tuned on, then shapes they were not tuned on
+# (other aspect ratios, non-power-of-two multiples of the tile, rows beyond the register-resident kernels, shapes
+# that miss the fast path's alignment and take the generic kernels, short and very long rows).
+SWEEP_SHAPES = [
+    ("tuned", "bf16", 65536, 2048, 8192), ("tuned", "bf16", 8192, 1024, 4096), ("tuned", "bf16", 16384, 4096, 4096),
+    ("untuned", "bf16", 32768, 1024, 1024), ("untuned", "bf16", 16384, 1536, 3072), ("untuned", "bf16", 4096, 4096, 16384),
+    ("untuned", "bf16", 2048, 8192, 512), ("untuned", "bf16", 131072, 512, 2048), ("untuned", "bf16", 8192, 2048, 32768),
+    ("untuned", "bf16", 10000, 1000, 3000), ("untuned", "bf16", 16384, 1024, 64), ("untuned", "bf16", 4096, 1024, 8200),
+    ("tuned", "f32", 3001, 771, 1537), ("untuned", "f32", 4096, 1024, 2048),
+]
+
+
+def run_sweep(steps: int, warmup: int):
+    """Throughput over SWEEP_SHAPES (text table, one line per shape): where the tuned tiling over-fits."""
+    import torch
+    from paper_2509_14279_amd import api
+    dev = torch.device("cuda:0")
+    ev = HipEvents()
+    nph = len(api.FDL_PHASES)
+    print(f"{'kind':8s} {'dtype':5s} {'M':>7s} {'K':>6s} {'N':>6s} {'ms/step':>9s} {'TFLOP/s':>8s}  " +
+          " ".join(f"{n:>7s}" for n in api.FDL_PHASES))
+    for kind, dtype, M, K, N in SWEEP_SHAPES:
+        dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        g = torch.Generator(device=dev)
+        g.manual_seed(M + 3 * K + 7 * N)
+        rnd = lambda *sh: torch.randn(*sh, device=dev, generator=g)
+        X = rnd(M, K).to(dt); W = (rnd(N, K) / K ** 0.5).to(dt); dY = rnd(M, N).to(dt)
+        b = rnd(N) * 0.14; gm = 1 + 0.3 * rnd(N); bt = 0.3 * rnd(N)
+        Y = torch.empty(M, N, device=dev, dtype=dt); Z = torch.empty_like(Y)
+        mean = torch.empty(M, device=dev); rstd = torch.empty(M, device=dev)
+        dX = torch.empty(M, K, device=dev, dtype=dt); dW = torch.empty(N, K, device=dev, dtype=dt)
+        db = torch.empty(N, device=dev); dg = torch.empty(N, device=dev); dbt = torch.empty(N, device=dev)
+        ws = torch.empty(api.fdl_workspace_bytes(dtype, M, K, N), dtype=torch.uint8, device=dev)
+        st = torch.cuda.current_stream()
+
+        def step():
+            api.fdl_forward(dtype, X, W, b, gm, bt, 1e-5, Y, Z, mean, rstd, ws, st)
+            api.fdl_backward(dtype, dY, X, W, gm, Z, mean, rstd, dX, dW, db, dg, dbt, ws, st)
+
+        for _ in range(warmup):
+            step()
+        sets = [[ev.create() for _ in range(2 * nph)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            api.fdl_set_phase_events(sets[k])
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        api.fdl_set_phase_events(None)
+        ph = [sum(ev.elapsed_ms(s[2 * p], s[2 * p + 1]) for s in sets) / steps for p in range(nph)]
+        for s in sets:
+            for e in s:
+                ev.destroy(e)
+        print(f"{kind:8s} {dtype:5s} {M:7d} {K:6d} {N:6d} {ms:9.3f} {6.0 * M * N * K / (ms * 1e-3) / 1e12:8.1f}  " +
+              " ".join(f"{x:7.3f}" for x in ph), flush=True)
+        del X, W, dY, Y, Z, dX, dW, ws
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +218,8 @@ def main():
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference point for HBM byte counters)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="print a throughput table over tuned and untuned shapes instead of the JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on exactly one GPU (got --gpus {args.gpus}); "
@@ -172,6 +233,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
+    if args.sweep:
+        run_sweep(args.steps, args.warmup)
+        return
     cfg = I.CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
