@@ -408,23 +408,36 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
 }
 
 // ------------------------------------------------------------------------------------------------
-// B2: colpart [groups][3][N] -> dbeta, dgamma, db.  64 consecutive columns per workgroup (coalesced),
-// the groups split over the 4 wavefronts, fp64 sums.
+// B2: colpart [groups][3][N] -> dbeta, dgamma, db.  64 consecutive columns per workgroup (coalesced), the groups
+// dealt over the 16 wavefronts, four independent partial sums per thread so that several loads are in flight
+// (the phase is pure latency: a few tens of MB), fp64 sums in a fixed order.
 template <class C>
-__global__ __launch_bounds__(256) void b2_kernel(int64_t N, int groups, const C* __restrict__ colpart,
-                                                 float* __restrict__ dbeta, float* __restrict__ dgamma,
-                                                 float* __restrict__ db) {
-  __shared__ double red[4][64];
+__global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C* __restrict__ colpart,
+                                                  float* __restrict__ dbeta, float* __restrict__ dgamma,
+                                                  float* __restrict__ db) {
+  constexpr int kSlices = 16;
+  __shared__ double red[kSlices][64];
   const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
   const int64_t col = (int64_t)blockIdx.x * 64 + lane;
   const int which = blockIdx.y;
-  double acc = 0.0;
-  if (col < N)
-    for (int g = slice; g < groups; g += 4) acc += (double)colpart[((int64_t)g * 3 + which) * N + col];
-  red[slice][lane] = acc;
+  double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+  if (col < N) {
+    const C* src = colpart + (int64_t)which * N + col;
+    const int64_t gstride = 3 * N;
+    int g = slice;
+    for (; g + 3 * kSlices < groups; g += 4 * kSlices) {
+      const C v0 = src[(int64_t)g * gstride], v1 = src[(int64_t)(g + kSlices) * gstride];
+      const C v2 = src[(int64_t)(g + 2 * kSlices) * gstride], v3 = src[(int64_t)(g + 3 * kSlices) * gstride];
+      a0 += (double)v0; a1 += (double)v1; a2 += (double)v2; a3 += (double)v3;
+    }
+    for (; g < groups; g += kSlices) a0 += (double)src[(int64_t)g * gstride];
+  }
+  red[slice][lane] = (a0 + a1) + (a2 + a3);
   __syncthreads();
   if (slice == 0 && col < N) {
-    const double t = red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane];
+    double t = 0.0;
+#pragma unroll
+    for (int w = 0; w < kSlices; w++) t += red[w][lane];
     float* out = which == 0 ? dbeta : (which == 1 ? dgamma : db);
     out[col] = (float)t;
   }
@@ -586,8 +599,8 @@ void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, const void* dY, c
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
                hipStream_t s) {
   const dim3 grid((unsigned)((N + 63) / 64), 3);
-  if (dt == kF32) hipLaunchKernelGGL((b2_kernel<double>), grid, dim3(256), 0, s, N, groups, (const double*)colpart, dbeta, dgamma, db);
-  else hipLaunchKernelGGL((b2_kernel<float>), grid, dim3(256), 0, s, N, groups, (const float*)colpart, dbeta, dgamma, db);
+  if (dt == kF32) hipLaunchKernelGGL((b2_kernel<double>), grid, dim3(1024), 0, s, N, groups, (const double*)colpart, dbeta, dgamma, db);
+  else hipLaunchKernelGGL((b2_kernel<float>), grid, dim3(1024), 0, s, N, groups, (const float*)colpart, dbeta, dgamma, db);
 }
 
 }  // namespace fdl
