@@ -213,7 +213,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="index into the five seeded configurations")
-    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the workload the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=32768,
+                    help="rows of the workload the CPU oracle is timed on (about 15 s of CPU work at the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-eager", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
