@@ -3,9 +3,8 @@
 //     D[i][j] = sum_r P(i,r) * Q(j,r)      stored as C[j][i]   (C row-major, leading dimension I)
 //
 // P feeds the MFMA "A" side, Q the "B" side, so a lane ends up with 4 consecutive i (output columns) of one
-// output row j in adjacent accumulator registers: rows of C are written with 8-byte stores, and a row
-// reduction over i (the LayerNorm statistics of the forward pass) is a sum inside the lane plus one
-// cross-half exchange.
+// output row j in adjacent accumulator registers, and a row reduction over i (the LayerNorm statistics, where
+// the forward pass takes them here) is a sum inside the lane plus one cross-half exchange.
 //
 //   F1  Z[m][n]  = sum_k X[m][k] W[n][k] + b[n]   P = W (i = n, r-contiguous)   Q = X  (j = m, r-contiguous)
 //   B3  dX[m][k] = sum_n dZ[m][n] W[n][k]         P = W (i = k, r = n major)    Q = dZ (j = m, r-contiguous)
@@ -18,7 +17,9 @@
 // (16 bytes per lane, no staging registers); the loads of slice kt+NS are issued as soon as slice kt's stage is
 // released and stay in flight for NS-1 slice times while the MFMAs of the other stages run.  Workgroups are
 // persistent (one per CU): the first slices of a workgroup's next tile are fetched during the last slices of its
-// current one, and output tiles leave through a small LDS staging area as 256-byte row segments.
+// current one, and output tiles leave through a small LDS staging area as 256-byte row segments (short row
+// segments cost write bandwidth: 8 or 16 bytes per lane straight from the registers measured 3 to 18 % slower).
+// The number of slices per tile is a multiple of NS, so every slice's LDS stage is a compile-time constant.
 //
 // LDS tile layouts (XOR-swizzled by choosing which global chunk a lane fetches, since a direct load lands at
 // base + lane*16):
