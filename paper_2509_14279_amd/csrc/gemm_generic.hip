@@ -11,10 +11,11 @@
 // output element).
 //
 // Storage fp32  -> operands widened to fp64 in registers, v_mfma_f64_16x16x4_f64, fp64 accumulators.
-// Storage bf16  -> operands widened to fp32 at the global load, v_mfma_f32_16x16x4_f32, fp32 accumulators.
-// Both instructions take one A and one B value per lane (row/col = lane%16, k = lane/16); the kernel
-// assigns reduction index 4*(lane/16)+s to MFMA step s of a 16-deep slice for A and B alike, which lets an
-// r-contiguous operand be read from LDS with one 16-byte read per four MFMA steps.
+// Storage bf16  -> operands widened to fp32 at the global load (one LDS layout for both storage types), packed back
+//                  to bf16 at the fragment (exact), v_mfma_f32_16x16x16_bf16, fp32 accumulators.
+// A lane's fragment is the four reduction indices 4*(lane/16)+s, s = 0..3, of a 16-deep slice for A and B alike
+// (row/col = lane%16): four steps of the fp64 instruction, which takes one value per lane and step, or the
+// operand of one bf16 instruction; an r-contiguous operand is read from LDS with one 16-byte read per fragment.
 //
 // Workgroup: 256 threads = 4 waves as 2x2; wave tile (16*WB)^2; block tile (32*WB)^2; 16-deep reduction
 // slices, double-buffered in LDS with the next slice's global loads in flight during the MFMAs.
@@ -39,6 +40,12 @@ template <> struct Mma<double> {
   static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
     return __builtin_amdgcn_mfma_f64_16x16x4f64((double)a, (double)b, c, 0, 0, 0);
   }
+  // the lane's four reduction steps of a 16-deep slice
+  static __device__ __forceinline__ acc_t mma4(const float (&a)[4], const float (&b)[4], acc_t c) {
+#pragma unroll
+    for (int s = 0; s < 4; s++) c = mma(a[s], b[s], c);
+    return c;
+  }
   // accumulator register r of lane l holds output row 4r + l/16, column l%16
   static __device__ __forceinline__ int row(int lane, int r) { return r * 4 + (lane >> 4); }
 };
@@ -46,6 +53,16 @@ template <> struct Mma<float> {
   typedef f32x4 acc_t;
   static __device__ __forceinline__ acc_t mma(float a, float b, acc_t c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+  }
+  // The values are bf16 numbers widened to fp32 on their way through LDS, so packing the lane's four reduction
+  // steps back into bf16 is exact and one v_mfma_f32_16x16x16_bf16 (k = 4 (lane/16) + e, the same assignment of
+  // reduction indices to lanes) does the work of four fp32 steps at sixteen times the rate.
+  static __device__ __forceinline__ acc_t mma4(const float (&a)[4], const float (&b)[4], acc_t c) {
+    typedef __attribute__((ext_vector_type(4))) short s16x4;
+    bf16x4 pa, pb;
+#pragma unroll
+    for (int s = 0; s < 4; s++) { pa[s] = (bf16_t)a[s]; pb[s] = (bf16_t)b[s]; }
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, pa), __builtin_bit_cast(s16x4, pb), c, 0, 0, 0);
   }
   // accumulator register r of lane l holds output row 4(l/16) + r, column l%16
   static __device__ __forceinline__ int row(int lane, int r) { return (lane >> 4) * 4 + r; }
@@ -168,11 +185,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
 #pragma unroll
     for (int b = 0; b < WB; b++) OpB::frag(lds[cur][1], wj * 16 * WB + b * 16 + l16, g, fb[b]);
 #pragma unroll
-    for (int s = 0; s < 4; s++)
+    for (int a = 0; a < WB; a++)
 #pragma unroll
-      for (int a = 0; a < WB; a++)
-#pragma unroll
-        for (int b = 0; b < WB; b++) acc[a][b] = Mma<AccT>::mma(fa[a][s], fb[b][s], acc[a][b]);
+      for (int b = 0; b < WB; b++) acc[a][b] = Mma<AccT>::mma4(fa[a], fb[b], acc[a][b]);
     if (more) {
       OpA::stash(lds[cur ^ 1][0], tid, ra);
       OpB::stash(lds[cur ^ 1][1], tid, rb);
