@@ -83,6 +83,53 @@ template <> struct Gauss<float> {
 template <class C> __device__ __forceinline__ C gelu(C z) { return Gauss<C>::gelu_of(z, Gauss<C>::cdf(z)); }
 
 // ---------------------------------------------------------------------------------------------
+// Exact Phi for bf16 arguments, from a table in LDS.  A bf16 number has 8 significant bits, so the magnitudes in
+// [2^-14, 16) are only 18 binades x 128 = 2304 values; for each of them the table holds
+//   H = Phi(|z|) - 1/2      and (kPair) Q = |z| phi(|z|),
+// both odd in z, as fp32 roundings of an fp64 evaluation.  Smaller magnitudes use the first entry (H, Q < 2.5e-5)
+// and larger ones the last (H = 1/2, Q = 0 to fp32).  A lookup is: clamp the magnitude bits, one LDS read, copy
+// the sign of z onto the entries - five integer instructions instead of the eleven of the polynomial, and
+// GELU(z) = z (1/2 + sign(z) H) carries no approximation error beyond fp32 rounding.  Every workgroup builds
+// its own copy (a few fp64 evaluations per thread), so there is no global state to initialise.
+template <bool kPair> struct GaussTable {
+  static constexpr uint32_t kLo = 0x3880u;          // bf16 bits of 2^-14
+  static constexpr uint32_t kHi = 0x417fu;          // bf16 bits of the largest bf16 number below 16
+  static constexpr int kEntries = (int)(kHi - kLo) + 1;
+  static constexpr int kEntryBytes = kPair ? 8 : 4;
+  static constexpr int kBytes = kEntries * kEntryBytes;
+
+  // tbl: LDS; every thread of the workgroup calls this (followed by a barrier at the caller)
+  static __device__ __forceinline__ void build(float* tbl, int tid, int nthreads) {
+    for (int i = tid; i < kEntries; i += nthreads) {
+      const double z = (double)__builtin_bit_cast(float, (kLo + (uint32_t)i) << 16);
+      const double H = 0.5 * erf(z * 0.70710678118654752440);
+      if (kPair) {
+        tbl[2 * i] = (float)H;
+        tbl[2 * i + 1] = (float)(z * exp(-0.5 * z * z) * 0.39894228040143267794);
+      } else {
+        tbl[i] = (float)H;
+      }
+    }
+  }
+  // LDS address of the entry for the bf16 number whose bits (sign included or not) are in the low 16 bits of
+  // `bits`: clamped magnitude bits times the entry size plus origin(table address), in three instructions
+  static __device__ __forceinline__ uint32_t origin(uint32_t table_lds_address) {
+    return table_lds_address - kLo * (uint32_t)kEntryBytes;     // wraps; the sum below is the true address again
+  }
+  static __device__ __forceinline__ uint32_t address_of(uint32_t bits, uint32_t org) {
+    uint32_t mag = bits & 0x7fffu;
+    mag = mag < kLo ? kLo : mag;
+    mag = mag > kHi ? kHi : mag;
+    return mag * (uint32_t)kEntryBytes + org;
+  }
+  // sign(z) |h|: magnitude bits of h, sign bit of z
+  static __device__ __forceinline__ float with_sign_of(float h, float z) {
+    return __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, h) & 0x7fffffffu) |
+                                         (__builtin_bit_cast(uint32_t, z) & 0x80000000u));
+  }
+};
+
+// ---------------------------------------------------------------------------------------------
 // Vector access helpers: V consecutive storage elements <-> V values of the arithmetic type.
 template <class T, int V> struct VecIO;
 

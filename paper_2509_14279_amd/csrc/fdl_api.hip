@@ -223,7 +223,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   {
     PhaseTimer t(FDL_PHASE_B1, s);
     if (p.b1_fused) {
-      launch_b1_fused((int)dt, M, N, p.b1_groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+      launch_b1_fused((int)dt, M, N, p.b1_groups, p.f2_rows != 0, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
     } else {
       launch_b1a((int)dt, M, N, dY, Zsave, gamma, mean, rstd, c12, s);
       launch_b1b((int)dt, M, N, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);

@@ -78,7 +78,8 @@ void launch_b1b(int dt, int64_t M, int64_t N, int rows_per_group, int groups, co
                 void* colpart, hipStream_t s);
 // fused single pass (row held in registers); returns false if this N is not supported by it
 bool b1_fused_supported(int dt, int64_t N);
-void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, const void* dY, const void* Zsave,
+// table: evaluate GELU from the LDS table, as the forward pass did (bf16, plan.f2_rows); else as the other kernels do
+void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, bool table, const void* dY, const void* Zsave,
                      const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart,
                      hipStream_t s);
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,

@@ -90,6 +90,11 @@ __global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float
 #pragma clang fp contract(off)
   extern __shared__ f32x4 gb[];   // [CH][4][64]: gamma[0:4], gamma[4:8], beta[0:4], beta[4:8] of vector c*64 + lane
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  typedef GaussTable<false> GT;
+  typedef __attribute__((address_space(3))) float lds_float;
+  float* htab = reinterpret_cast<float*>(gb + CH * 4 * 64);           // Phi - 1/2 for every bf16 magnitude
+  const uint32_t horg = GT::origin((uint32_t)(uintptr_t)(const lds_float*)htab);
+  GT::build(htab, threadIdx.x, NT);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: row addresses stay scalar
   const int nvec = (int)(N >> 3);
@@ -115,44 +120,49 @@ __global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float
   }
 
   u32x4 raw[CH];
-  auto fetch = [&](int64_t r) {
-    const bf16_t* zr = Z + (r < M ? r : M - 1) * N;   // past the last row: a harmless re-read, never used
-#pragma unroll
-    for (int c = 0; c < CH; c++) {
-      if (FULL) {
-        // scalar base per vector + one shared per-lane offset (the immediate offset field reaches only 4 KB)
-        const bf16_t* zc = zr + c * 512;
-        asm("" : "+s"(zc));
-        raw[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(zc + lane * 8));
-      } else {
-        raw[c] = *reinterpret_cast<const u32x4*>(zr + voff[c]);
-      }
+  // vector c of row r (past the last row: a harmless re-read of the last one, never used)
+  auto fetch1 = [&](int c, const bf16_t* zr) {
+    if (FULL) {
+      // scalar base per vector + one shared per-lane offset (the immediate offset field reaches only 4 KB)
+      const bf16_t* zc = zr + c * 512;
+      asm("" : "+s"(zc));
+      raw[c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(zc + lane * 8));
+    } else {
+      raw[c] = *reinterpret_cast<const u32x4*>(zr + voff[c]);
     }
   };
   int64_t row = (int64_t)blockIdx.x * (NT / 64) + wave;
-  fetch(row);
+  {
+    const bf16_t* zr = Z + (row < M ? row : M - 1) * N;
+#pragma unroll
+    for (int c = 0; c < CH; c++) fetch1(c, zr);
+  }
   for (; row < M; row += nw) {
     float a[CH][8];
     float sum = 0.0f;
+    const bf16_t* znext = Z + (row + nw < M ? row + nw : M - 1) * N;
 #pragma unroll
     for (int c = 0; c < CH; c++) {
 #pragma unroll
       for (int h = 0; h < 4; h++) {
         const uint32_t w = FULL ? raw[c][h] : (raw[c][h] & keep[c]);
-        a[c][2 * h] = gelu<float>(__builtin_bit_cast(float, w << 16));              // bf16 -> fp32 is a 16-bit shift
-        a[c][2 * h + 1] = gelu<float>(__builtin_bit_cast(float, w & 0xffff0000u));
+        const float z0 = __builtin_bit_cast(float, w << 16);                        // bf16 -> fp32 is a 16-bit shift
+        const float z1 = __builtin_bit_cast(float, w & 0xffff0000u);
+        const float h0 = *(const lds_float*)(uintptr_t)GT::address_of(w, horg);
+        const float h1 = *(const lds_float*)(uintptr_t)GT::address_of(w >> 16, horg);
+        a[c][2 * h] = z0 * (0.5f + GT::with_sign_of(h0, z0));                       // GELU(z) = z Phi(z)
+        a[c][2 * h + 1] = z1 * (0.5f + GT::with_sign_of(h1, z1));
         sum += a[c][2 * h];
         sum += a[c][2 * h + 1];
       }
-      // eight polynomial evaluations side by side are enough to cover the arithmetic latency; interleaving all
-      // of a row's would keep three temporaries per element alive
+      // One vector at a time (interleaving all of a row's evaluations would keep their temporaries alive), and as
+      // soon as a vector is unpacked its registers take the same vector of the wavefront's next row: the loads
+      // trickle out through the whole first sweep and have the rest of the row's work to arrive, while a row of
+      // packed values and a row of fp32 values are all a lane ever holds.
+      __builtin_amdgcn_sched_barrier(0);
+      fetch1(c, znext);
       __builtin_amdgcn_sched_barrier(0);
     }
-    // the next row is requested only once this row has been unpacked, so that a row of packed values and a row
-    // of fp32 values are all a lane ever holds
-    __builtin_amdgcn_sched_barrier(0);
-    fetch(row + nw);
-    __builtin_amdgcn_sched_barrier(0);
     const float mu = wave_sum(sum) * inv_n;
     float m2 = 0.0f;
 #pragma unroll
@@ -310,7 +320,11 @@ template <class T, int V> __device__ __forceinline__ typename RawVec<T, V>::type
   return r;
 }
 
-template <class T, int V, int S, int NT>
+// TAB (bf16 only): Phi and z phi(z) come from the LDS table (exact for bf16 arguments) instead of the polynomial
+// and the hardware exponential.  The backward pass must evaluate GELU exactly as the forward pass that produced
+// mean and rstd did - for a constant row, rstd = eps^-1/2 multiplies any difference between the two into Ahat -
+// so the launcher selects TAB if and only if the forward pass normalised with the table.
+template <class T, int V, int S, int NT, bool TAB>
 __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, const T* __restrict__ dY,
                                                        const T* __restrict__ Z, const float* __restrict__ gamma,
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
@@ -318,7 +332,16 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
                                                        typename ComputeOf<T>::type* __restrict__ colpart) {
   typedef typename ComputeOf<T>::type C;
   typedef typename RawVec<T, V>::type raw_t;
+  typedef GaussTable<true> GT;
+  typedef __attribute__((address_space(3))) f32x2 lds_f32x2;
   __shared__ C red[2][NT / 64][2];
+  __shared__ __attribute__((aligned(8))) float gtab[TAB ? 2 * GT::kEntries : 2];
+  uint32_t gorg = 0;
+  if (TAB) {
+    GT::build(gtab, threadIdx.x, NT);
+    gorg = GT::origin((uint32_t)(uintptr_t)(const lds_f32x2*)gtab);
+    __syncthreads();
+  }
   int64_t col[S];
   bool ok[S];
   C gm[S][V], accb[S][V], accg[S][V], accz[S][V];
@@ -363,10 +386,18 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
       for (int v = 0; v < V; v++) {
         const C z = raw_get<T, V, C>(bz[buf][s], v);
         const C dy = raw_get<T, V, C>(bdy[buf][s], v);
-        C Phi, phi;
-        Gauss<C>::eval(z, Phi, phi);
-        ah[s][v] = Gauss<C>::gelu_of(z, Phi) * rs + nmr;   // (A - mean) rstd, one fused multiply-add
-        gp[s][v] = (Phi + z * phi) * rs;
+        if constexpr (TAB) {
+          const uint32_t zbits = __builtin_bit_cast(uint32_t, (float)z) >> 16;      // the bf16 bits of z
+          const f32x2 e = *(const lds_f32x2*)(uintptr_t)GT::address_of(zbits, gorg);
+          const float Phi = 0.5f + GT::with_sign_of(e[0], (float)z);
+          ah[s][v] = ((float)z * Phi) * rs + nmr;
+          gp[s][v] = (Phi + GT::with_sign_of(e[1], (float)z)) * rs;
+        } else {
+          C Phi, phi;
+          Gauss<C>::eval(z, Phi, phi);
+          ah[s][v] = Gauss<C>::gelu_of(z, Phi) * rs + nmr;   // (A - mean) rstd, one fused multiply-add
+          gp[s][v] = (Phi + z * phi) * rs;
+        }
         g[s][v] = dy * gm[s][v];
         s1 += g[s][v];
         s2 += g[s][v] * ah[s][v];
@@ -507,17 +538,17 @@ inline bool fused_shape(int64_t N, int V, bool vec, FusedShape* out) {
   return false;
 }
 
-template <class T> void b1_fused_impl(int64_t M, int64_t N, int groups, const void* dY, const void* Z,
-                                      const float* gamma, const float* mean, const float* rstd, void* dZ,
-                                      void* colpart, hipStream_t s) {
+template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int groups, const void* dY, const void* Z,
+                                                const float* gamma, const float* mean, const float* rstd, void* dZ,
+                                                void* colpart, hipStream_t s) {
   typedef typename ComputeOf<T>::type C;
   constexpr int VMAX = 16 / (int)sizeof(T);
   const int V = vec_width<T>(dY, Z, dZ, N);
   FusedShape fs;
   if (!fused_shape(N, V, V == VMAX, &fs)) return;   // callers check b1_fused_supported first
-#define FDL_B1F(VV, SS, NTT)                                                                                         \
-  hipLaunchKernelGGL((b1_fused_kernel<T, VV, SS, NTT>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N, (const T*)dY, \
-                     (const T*)Z, gamma, mean, rstd, (T*)dZ, (C*)colpart)
+#define FDL_B1F(VV, SS, NTT)                                                                                       \
+  hipLaunchKernelGGL((b1_fused_kernel<T, VV, SS, NTT, TAB>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N,           \
+                     (const T*)dY, (const T*)Z, gamma, mean, rstd, (T*)dZ, (C*)colpart)
   if (V == VMAX) {
     if (fs.nt == 256) FDL_B1F(VMAX, 1, 256); else if (fs.nt == 512) FDL_B1F(VMAX, 1, 512); else FDL_B1F(VMAX, 1, 1024);
   } else {
@@ -542,6 +573,20 @@ void launch_f2(int dt, int64_t M, int64_t N, const void* Zsave, const float* mea
   else f2_impl<bf16_t>(M, N, Zsave, mean, rstd, gamma, beta, Y, s);
 }
 
+// one instantiation: gamma/beta (4 KB per 512 columns) plus the Phi table can exceed the default 64 KB of dynamic LDS
+template <int CH, bool FULL, int NT>
+void launch_f2_rows_one(int64_t wgs, hipStream_t s, int64_t M, int64_t N, float eps, const bf16_t* Z, const float* gamma,
+                        const float* beta, bf16_t* Y, float* mean, float* rstd) {
+  constexpr size_t kLds = (size_t)CH * 4096 + GaussTable<false>::kBytes;
+  static bool configured = false;
+  auto kern = f2_rows_kernel<CH, FULL, NT>;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(NT), kLds, s, M, N, eps, Z, gamma, beta, Y, mean, rstd);
+}
+
 bool f2_rows_supported(int dt, int64_t N) { return dt == kBF16 && N % 8 == 0 && N <= 8192; }
 
 void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const float* gamma, const float* beta, void* Y,
@@ -556,7 +601,7 @@ void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const fl
   const int64_t cap = 256 * (16 / ch);
   if (wgs > cap) wgs = cap;
 #define FDL_F2R(CHH, FULL, NTT)                                                                                    \
-  hipLaunchKernelGGL((f2_rows_kernel<CHH, FULL, NTT>), dim3((unsigned)wgs), dim3(NTT), (size_t)CHH * 4096, s, M, N,   \
+  launch_f2_rows_one<CHH, FULL, NTT>(wgs, s, M, N,                                                                      \
                      eps, (const bf16_t*)Zsave, gamma, beta, (bf16_t*)Y, mean, rstd)
   if (full) {
     if (ch == 2) FDL_F2R(2, true, 512); else if (ch == 4) FDL_F2R(4, true, 512);
@@ -590,10 +635,11 @@ bool b1_fused_supported(int dt, int64_t N) {
   return fused_shape(N, V, V == vmax, &fs);
 }
 
-void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, const void* dY, const void* Zsave, const float* gamma,
-                     const float* mean, const float* rstd, void* dZ, void* colpart, hipStream_t s) {
-  if (dt == kF32) b1_fused_impl<float>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
-  else b1_fused_impl<bf16_t>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, bool table, const void* dY, const void* Zsave,
+                     const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart, hipStream_t s) {
+  if (dt == kF32) b1_fused_impl<float, false>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else if (table) b1_fused_impl<bf16_t, true>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else b1_fused_impl<bf16_t, false>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
 }
 
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
