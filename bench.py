@@ -149,13 +149,13 @@ def torch_eager_ms(cfg, dev_t, iters=5):
 
 
 # Shapes for --sweep: the seeded configurations the kernels were tuned on, then shapes they were not tuned on
-# (other aspect ratios, non-power-of-two multiples of the tile, rows beyond the register-resident kernels, shapes
-# that miss the fast path's alignment and take the generic kernels, short and very long rows).
+# (other aspect ratios, non-power-of-two multiples of the tile, rows beyond the register-resident kernels, a ragged
+# batch dimension, shapes that miss the fast path's alignment and take the generic kernels, short and very long rows).
 SWEEP_SHAPES = [
     ("tuned", "bf16", 65536, 2048, 8192), ("tuned", "bf16", 8192, 1024, 4096), ("tuned", "bf16", 16384, 4096, 4096),
     ("untuned", "bf16", 32768, 1024, 1024), ("untuned", "bf16", 16384, 1536, 3072), ("untuned", "bf16", 4096, 4096, 16384),
     ("untuned", "bf16", 2048, 8192, 512), ("untuned", "bf16", 131072, 512, 2048), ("untuned", "bf16", 8192, 2048, 32768),
-    ("untuned", "bf16", 10000, 1000, 3000), ("untuned", "bf16", 16384, 1024, 64), ("untuned", "bf16", 4096, 1024, 8200),
+    ("untuned", "bf16", 10000, 1024, 3072), ("untuned", "bf16", 50001, 2048, 4096), ("untuned", "bf16", 10000, 1000, 3000), ("untuned", "bf16", 16384, 1024, 64), ("untuned", "bf16", 4096, 1024, 8200),
     ("tuned", "f32", 3001, 771, 1537), ("untuned", "f32", 4096, 1024, 2048),
 ]
 

@@ -50,6 +50,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.stat_tiles = (int)((N + q.stat_tile_w - 1) / q.stat_tile_w);
   size_t off = 0;
   q.off_part = off; off += align256((size_t)q.stat_tiles * Mp * 8);
+  q.off_xtail = off; off += align256(q.f1_fast ? fast_f1_tail_bytes(M, K) : 0);
   q.fwd_bytes = off;
 
   // ---- backward
@@ -67,12 +68,16 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.b4_fast = dt == kBF16 && fast_b4_supported(M, K, N);
   q.b3_wb = pick_wb(Mp, K);
   q.b4_wb = pick_wb(N, K);
-  q.b4_split = q.b4_fast ? fast_b4_split(M, K, N) : 1;
+  q.b4_fast_rows = q.b4_fast ? fast_b4_rows(M) : 0;
+  q.b4_split = q.b4_fast ? fast_b4_split(q.b4_fast_rows, K, N) : 1;
+  const int b4_parts = q.b4_split + (q.b4_fast && q.b4_fast_rows < M ? 1 : 0);   // fp32 partial sums of dW
   off = 0;
-  q.off_dz = off; off += align256((size_t)Mp * N * ts);
+  // dZ: the fast dX kernel reads whole 256-row tiles, so the buffer is rounded up (the surplus rows are never
+  // written and never reach an output)
+  q.off_dz = off; off += align256((size_t)((Mp + 255) / 256 * 256) * N * ts);
   q.off_c12 = off; off += align256(q.b1_fused ? 0 : (size_t)2 * Mp * cs);
   q.off_colpart = off; off += align256((size_t)q.b1_groups * 3 * N * cs);
-  q.off_dwpart = off; off += align256(q.b4_split > 1 ? (size_t)q.b4_split * N * K * 4 : 0);
+  q.off_dwpart = off; off += align256(b4_parts > 1 ? (size_t)b4_parts * N * K * 4 : 0);
   q.bwd_bytes = off;
   q.bytes = q.fwd_bytes > q.bwd_bytes ? q.fwd_bytes : q.bwd_bytes;
   *p = q;
@@ -172,7 +177,7 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
   {
     PhaseTimer t(FDL_PHASE_F1, s);
     if (p.f1_fast) {
-      launch_fast_f1(M, K, N, X, W, b, Zsave, p.f2_rows ? nullptr : part, s);
+      launch_fast_f1(M, K, N, X, W, b, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
     } else {
       GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
       launch_generic_f1((int)dt, g, b, Zsave, part, s);
@@ -247,7 +252,19 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
     // B4: dW[N,K] = dZ^T[N,M] X[M,K]
     PhaseTimer t(FDL_PHASE_B4, s);
     if (p.b4_fast) {
-      launch_fast_b4(M, K, N, p.b4_split, dZ, X, dW, ws + p.off_dwpart, s);
+      // the fast kernel reduces over the first b4_fast_rows rows (a whole number of pipeline rounds); the few rows
+      // after them go through the generic kernel into one more fp32 partial sum
+      const int64_t Mf = p.b4_fast_rows;
+      const int extra = Mf < M ? 1 : 0;
+      float* dwpart = reinterpret_cast<float*>(ws + p.off_dwpart);
+      launch_fast_b4(Mf, K, N, p.b4_split, extra, dZ, X, dW, dwpart, s);
+      if (extra) {
+        const char* dZt = static_cast<const char*>(dZ) + (size_t)Mf * N * 2;
+        const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
+        GemmDesc g = {dZt, Xt, N, K, M - Mf, N, K, false, false, p.b4_wb};
+        launch_generic_store_f32(g, dwpart + (size_t)p.b4_split * N * K, s);
+        launch_fast_b4_reduce(K, N, p.b4_split + 1, dwpart, dW, s);
+      }
     } else {
       GemmDesc g = {dZ, X, N, K, M, N, K, false, false, p.b4_wb};
       launch_generic_store((int)dt, g, dW, s);

@@ -52,12 +52,14 @@ enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2, EPI_PARTIAL = 3 };
 
 struct FastParams {
   const bf16_t* P; const bf16_t* Q;
+  const bf16_t* Qtail;   // RAG: the Q rows of the last (partial) row tile as a padded 256-row copy, or null if Q
+                         //      itself has readable rows up to the end of that tile
   int64_t ldp, ldq;
   bf16_t* C;             // [J][I]
   float* Cpart;          // [split][J][I] fp32 (split > 1)
   const float* bias;     // [I]   (EPI_F1, EPI_BIAS)
   f32x2* part;           // [I/128][J]  (EPI_F1)
-  int I, J;
+  int I, J;              // J: valid output rows (RAG: any number >= 1; otherwise a multiple of 256)
   int tiles_i, tiles_j;
   int nkt;               // reduction slices per workgroup
   int split;
@@ -195,9 +197,13 @@ __device__ __forceinline__ TileCoord tile_coord(int L, int tiles_i, int tiles_j)
   return c;
 }
 
-template <bool P_RM, bool Q_RM, int EPI, int BK, int NS>
+// RAG: the number of output rows J is not a multiple of the tile (ragged batch dimension of F1 and B3).  The last
+// row tile then reads its Q rows from a padded copy (or from a Q buffer that is itself padded), computes the
+// surplus rows on whatever that padding holds - rows of a product are independent - and does not store them.
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_bf16_kernel(FastParams p) {
+  static_assert(!RAG || !Q_RM, "a ragged row count is supported for r-contiguous Q only");
   typedef Geo<BK> G;
   static_assert(NS * G::kStageBytes == kLdsStages, "stages must fill 128 KB");
   static_assert((NS == 2 || NS == 4) && (G::kSub & 1) == 0, "2 or 4 stages, even number of sub-slices");
@@ -245,6 +251,7 @@ void gemm_bf16_kernel(FastParams p) {
     return lp.wave_base(P_RM ? p.P + r_begin * p.ldp + i0 : p.P + (int64_t)i0 * p.ldp + r_begin, p.ldp, wave);
   };
   auto q_origin = [&](int j0) {
+    if (RAG && p.Qtail != nullptr && j0 == (p.tiles_j - 1) * kTile) return lq.wave_base(p.Qtail + r_begin, p.ldq, wave);
     return lq.wave_base(Q_RM ? p.Q + r_begin * p.ldq + j0 : p.Q + (int64_t)j0 * p.ldq + r_begin, p.ldq, wave);
   };
 
@@ -477,6 +484,7 @@ void gemm_bf16_kernel(FastParams p) {
       for (int it = 0; it < 8; it++) {
         const u32x4 v = *(const lds_u32x4*)(wtile + roff[it & 3] + (it >> 2) * 4096);
         u32x4* dst = reinterpret_cast<u32x4*>(cbase + (int64_t)(it * 4) * p.I * 2 + svoff);
+        if (RAG && j0 + wj * 128 + b * 32 + it * 4 + e_rq >= p.J) continue;   // a row past the end
         // the forward output (Zsave, far larger than the caches) is streamed past them so that it does not evict
         // the operand panels the XCD's workgroups share; the smaller gradient outputs gain nothing from that
         if (kBias) __builtin_nontemporal_store(v, dst);
@@ -551,7 +559,7 @@ void gemm_bf16_kernel(FastParams p) {
             m2 = __builtin_fmaf(d, d, m2);
           }
         m2 += __shfl_xor(m2, 32, kWave);
-        if (e_half == 0) {
+        if (e_half == 0 && (!RAG || j < p.J)) {
           f32x2 o; o[0] = mean; o[1] = m2;
           p.part[(int64_t)stat_tile * p.J + j] = o;
         }
@@ -581,9 +589,22 @@ __global__ __launch_bounds__(256) void reduce_split_kernel(const float* __restri
   *reinterpret_cast<bf16x4*>(out + i) = o;
 }
 
-template <bool P_RM, bool Q_RM, int EPI, int BK, int NS> void launch(const FastParams& p, hipStream_t s) {
+// Padded copy of the rows [row0, rows) of a row-major matrix: 256 rows, zeros past the end.
+__global__ __launch_bounds__(256) void copy_tail_rows_kernel(const bf16_t* __restrict__ src, int64_t rows, int64_t ld,
+                                                             int64_t row0, bf16_t* __restrict__ dst) {
+  const int64_t n8 = (int64_t)kTile * ld / 8;   // ld is a multiple of 8 on this path
+  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += (int64_t)gridDim.x * 256) {
+    const int64_t r = (v * 8) / ld;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (row0 + r < rows) x = *reinterpret_cast<const u32x4*>(src + row0 * ld + v * 8);
+    *reinterpret_cast<u32x4*>(dst + v * 8) = x;
+  }
+}
+
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG = false>
+void launch(const FastParams& p, hipStream_t s) {
   static bool configured = false;   // raise the dynamic LDS limit once per kernel
-  auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI, BK, NS>;
+  auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI, BK, NS, RAG>;
   if (!configured) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     configured = true;
@@ -612,37 +633,57 @@ template <bool P_RM, bool Q_RM, int EPI, int BK, int NS> void launch(const FastP
 constexpr int kF1BK = FDL_F1_BK, kB3BK = FDL_B3_BK, kB4BK = FDL_B4_BK;
 constexpr int stages_of(int bk) { return kLdsStages / (2 * kTile * bk * 2); }
 
-bool dims_ok(int64_t I, int64_t J, int64_t R, int bk) {
-  return I > 0 && J > 0 && R > 0 && I % kTile == 0 && J % kTile == 0 && R % (stages_of(bk) * bk) == 0 &&
-         I <= (1 << 24) && J <= (1 << 24) && (I / kTile) * (J / kTile) <= (1 << 30);
+// ragged_j: J may be any number from kMinRaggedRows up (F1, B3: J = M); otherwise a multiple of the tile
+constexpr int64_t kMinRaggedRows = 128;
+bool dims_ok(int64_t I, int64_t J, int64_t R, int bk, bool ragged_j = false) {
+  const int64_t tj = (J + kTile - 1) / kTile;
+  return I > 0 && J > 0 && R > 0 && I % kTile == 0 && (ragged_j ? J >= kMinRaggedRows : J % kTile == 0) &&
+         R % (stages_of(bk) * bk) == 0 && I <= (1 << 24) && J <= (1 << 24) && (I / kTile) * tj <= (1 << 30);
 }
 
 }  // namespace
 
-bool fast_f1_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(N, M, K, kF1BK); }
-bool fast_b3_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, M, N, kB3BK); }
-bool fast_b4_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, N, M, kB4BK); }
+bool fast_f1_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(N, M, K, kF1BK, true); }
+bool fast_b3_supported(int64_t M, int64_t K, int64_t N) { return dims_ok(K, M, N, kB3BK, true); }
+// dW on the fast kernel: the whole reduction if M is a whole number of pipeline rounds, else its first
+// fast_b4_rows(M) rows (the caller adds the remaining rows' contribution)
+int64_t fast_b4_rows(int64_t M) { const int64_t u = (int64_t)kB4BK * stages_of(kB4BK); return M / u * u; }
+bool fast_b4_supported(int64_t M, int64_t K, int64_t N) {
+  return fast_b4_rows(M) >= 128 && dims_ok(K, N, fast_b4_rows(M), kB4BK);
+}
 int fast_f1_stat_tile_w() { return 128; }
+size_t fast_f1_tail_bytes(int64_t M, int64_t K) { return M % kTile ? (size_t)kTile * K * 2 : 0; }
 
-// part != nullptr: also emit the per-(row, 128-column tile) partial statistics of GELU(Zsave)
+// part != nullptr: also emit the per-(row, 128-column tile) partial statistics of GELU(Zsave).
+// xtail: fast_f1_tail_bytes(M, K) bytes of scratch for the padded copy of X's last rows (M not a multiple of 256)
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
-                    void* part, hipStream_t s) {
+                    void* part, void* xtail, hipStream_t s) {
   FastParams p = {};
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)X; p.ldp = K; p.ldq = K;
   p.C = (bf16_t*)Zsave; p.bias = bias; p.part = (f32x2*)part;
-  p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)(M / kTile);
+  p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
   p.nkt = (int)(K / kF1BK); p.split = 1;
-  if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
-  else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK)>(p, s);
+  if (M % kTile) {
+    p.Qtail = (const bf16_t*)xtail;
+    hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, K,
+                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail);
+    if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK), true>(p, s);
+    else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK), true>(p, s);
+  } else {
+    if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
+    else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK)>(p, s);
+  }
 }
 
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s) {
   FastParams p = {};
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = N;
   p.C = (bf16_t*)dX;
-  p.I = (int)K; p.J = (int)M; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)(M / kTile);
+  p.I = (int)K; p.J = (int)M; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
   p.nkt = (int)(N / kB3BK); p.split = 1;
-  launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK)>(p, s);
+  // ragged M: dZ is the library's own buffer and has readable rows up to the end of the last row tile
+  if (M % kTile) launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK), true>(p, s);
+  else launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK)>(p, s);
 }
 
 // Split of the reduction over M so that small dW outputs still fill the chip: each part keeps >= 512 rows.
@@ -651,23 +692,28 @@ int fast_b4_split(int64_t M, int64_t K, int64_t N) {
   const int64_t unit = (int64_t)kB4BK * stages_of(kB4BK);   // every part is a whole number of slice groups
   int split = 1;
   while (tiles * split * 2 <= 256 && M % (split * 2 * unit) == 0 && M / (split * 2) >= 512) split *= 2;
-  return split;
+  return split;   // M: the rows the fast kernel covers
 }
 
-void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dW, void* dwpart,
-                    hipStream_t s) {
+// dW from the first M rows (a whole number of pipeline rounds, see fast_b4_rows).  With split > 1 or extra > 0 the
+// kernel writes fp32 partial sums dwpart[0 .. split); the caller may add `extra` more partials behind them (the
+// rows the fast kernel does not cover) and then calls launch_fast_b4_reduce; otherwise dW is final on return.
+void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, const void* X, void* dW,
+                    void* dwpart, hipStream_t s) {
   FastParams p = {};
   p.P = (const bf16_t*)X; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = N;
   p.C = (bf16_t*)dW; p.Cpart = (float*)dwpart;
   p.I = (int)K; p.J = (int)N; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)(N / kTile);
   p.nkt = (int)(M / kB4BK / split); p.split = split;
-  if (split > 1) launch<true, true, EPI_PARTIAL, kB4BK, stages_of(kB4BK)>(p, s);
+  if (split > 1 || extra > 0) launch<true, true, EPI_PARTIAL, kB4BK, stages_of(kB4BK)>(p, s);
   else launch<true, true, EPI_STORE, kB4BK, stages_of(kB4BK)>(p, s);
-  if (split > 1) {
-    const int64_t n = N * K;
-    hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s,
-                       (const float*)dwpart, split, n, (bf16_t*)dW);
-  }
+  if (split > 1 && extra == 0) launch_fast_b4_reduce(K, N, split, dwpart, dW, s);
+}
+
+void launch_fast_b4_reduce(int64_t K, int64_t N, int parts, const void* dwpart, void* dW, hipStream_t s) {
+  const int64_t n = N * K;
+  hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s,
+                     (const float*)dwpart, parts, n, (bf16_t*)dW);
 }
 
 }  // namespace fdl

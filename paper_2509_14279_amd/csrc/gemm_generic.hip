@@ -25,7 +25,7 @@
 namespace fdl {
 namespace {
 
-enum { EPI_STORE = 0, EPI_F1 = 1 };
+enum { EPI_STORE = 0, EPI_F1 = 1, EPI_STORE_F32 = 2 };
 
 struct GemmParams {
   const void* A; const void* B; void* C;
@@ -198,7 +198,20 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
   // ------------------------------------------------------------------ epilogue
   const int64_t iw = i0 + wi * 16 * WB, jw = j0 + wj * 16 * WB;
   T* C = static_cast<T*>(p.C);
-  if (EPI == EPI_STORE) {
+  if (EPI == EPI_STORE_F32) {
+    float* Cf = static_cast<float*>(p.C);
+#pragma unroll
+    for (int a = 0; a < WB; a++)
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        const int64_t i = iw + a * 16 + Mma<AccT>::row(lane, r);
+#pragma unroll
+        for (int b = 0; b < WB; b++) {
+          const int64_t j = jw + b * 16 + l16;
+          if (i < p.I && j < p.J) Cf[i * p.J + j] = (float)acc[a][b][r];
+        }
+      }
+  } else if (EPI == EPI_STORE) {
 #pragma unroll
     for (int a = 0; a < WB; a++)
 #pragma unroll
@@ -297,6 +310,16 @@ void launch_generic_f1(int dt, const GemmDesc& g, const float* bias, void* Zsave
   GemmParams p = base_params(g);
   p.C = Zsave; p.bias = bias; p.part = static_cast<f32x2*>(part);
   if (dt == kF32) dispatch<float, EPI_F1>(g, p, s); else dispatch<bf16_t, EPI_F1>(g, p, s);
+}
+
+// only the operand orientation of the dW contraction (both operands indexed by the reduction row) is needed
+void launch_generic_store_f32(const GemmDesc& g, float* C, hipStream_t s) {
+  GemmParams p = base_params(g);
+  p.C = C;
+  p.a_vec = ((uintptr_t)g.A % 8 == 0) && (g.lda % 4 == 0);
+  p.b_vec = ((uintptr_t)g.B % 8 == 0) && (g.ldb % 4 == 0);
+  if (g.wb == 4) launch_one<bf16_t, false, false, 4, EPI_STORE_F32>(p, s);
+  else launch_one<bf16_t, false, false, 2, EPI_STORE_F32>(p, s);
 }
 
 void launch_generic_store(int dt, const GemmDesc& g, void* C, hipStream_t s) {

@@ -36,6 +36,8 @@ struct Plan {
   int b3_fast, b4_fast;
   int b3_wb, b4_wb;
   int b4_split;           // split of the reduction over M in B4 (fast kernel)
+  int64_t b4_fast_rows;   // rows of the reduction the fast kernel covers (the rest goes through the generic kernel)
+  size_t off_xtail;       // forward: padded copy of X's last rows (ragged M on the fast path)
   size_t off_dz;          // T [M][N]
   size_t off_c12;         // C [2][M]
   size_t off_colpart;     // C [groups][3][N]
@@ -61,6 +63,8 @@ struct GemmDesc {
 void launch_generic_f1(int dt, const GemmDesc& g, const float* bias, void* Zsave, void* part, hipStream_t s);
 // plain store: C [I][J] in the storage type
 void launch_generic_store(int dt, const GemmDesc& g, void* C, hipStream_t s);
+// plain store of the fp32 accumulators: C [I][J] float (bf16 storage; a partial sum for launch_fast_b4_reduce)
+void launch_generic_store_f32(const GemmDesc& g, float* C, hipStream_t s);
 
 // ---- row-wise / column-wise phases ------------------------------------------------------------
 void launch_stats_finalize(const void* part, int tiles, int tile_w, int64_t M, int64_t N, float eps,
@@ -86,15 +90,21 @@ void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta,
                hipStream_t s);
 
 // ---- bf16 fast path -----------------------------------------------------------------------------
+// F1 and B3 accept any M >= 128 (the last row tile may be partial); N, K as the tiles and the pipeline require.
 bool fast_f1_supported(int64_t M, int64_t K, int64_t N);
 bool fast_b3_supported(int64_t M, int64_t K, int64_t N);
+// B4 reduces over M: the fast kernel takes the first fast_b4_rows(M) rows; the rest (< 128) is left to the caller
 bool fast_b4_supported(int64_t M, int64_t K, int64_t N);
+int64_t fast_b4_rows(int64_t M);
 int fast_f1_stat_tile_w();
+size_t fast_f1_tail_bytes(int64_t M, int64_t K);
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
-                    void* part, hipStream_t s);
+                    void* part, void* xtail, hipStream_t s);
+// dZ must have readable rows up to the next multiple of 256
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s);
 int fast_b4_split(int64_t M, int64_t K, int64_t N);
-void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dW,
+void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, const void* X, void* dW,
                     void* dwpart, hipStream_t s);
+void launch_fast_b4_reduce(int64_t K, int64_t N, int parts, const void* dwpart, void* dW, hipStream_t s);
 
 }  // namespace fdl

@@ -95,6 +95,11 @@ def test_small_and_ragged_shapes(dtype, shape):
     # vector counts (exact fits 2048 / 8192; masked tails 4352 / 7936; 8448 takes the in-GEMM statistics instead)
     ("bf16", (256, 128, 2048)), ("bf16", (512, 128, 8192)), ("bf16", (256, 128, 4352)), ("bf16", (256, 128, 7936)),
     ("bf16", (256, 128, 8448)),
+    # ragged batch dimension on the bf16 fast path: partial last row tile in F1 and dX, dW = fast kernel over the first
+    # rows + generic kernel over the rest (1000 = 896 + 104; 130 = 128 + 2; 300 = 256 + 44), statistics in the GEMM
+    # epilogue for the long rows
+    ("bf16", (300, 256, 512)), ("bf16", (1000, 256, 768)), ("bf16", (130, 256, 256)), ("bf16", (385, 512, 1024)),
+    ("bf16", (129, 256, 8448)), ("bf16", (2500, 256, 2048)),
     # reduction lengths that are not a whole number of pipeline rounds fall back to the generic GEMM per contraction
     ("bf16", (256, 64, 512)), ("bf16", (320, 192, 256)),
 ])
