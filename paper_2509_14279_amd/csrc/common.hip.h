@@ -40,8 +40,9 @@ template <> __device__ __forceinline__ bf16_t to_storage<bf16_t, double>(double 
 //         two orders below what bf16 storage resolves.  GELU multiplies Phi by max(z, -4) instead of z so that
 //         the polynomial's residual at the left clamp (2.5e-5) is not scaled by an arbitrarily large |z|: the
 //         absolute error of GELU is <= 1.1e-4 for z < 0 and its relative error <= 2.6e-5 for z > 0.
-//         phi needs one hardware exp2.  Every kernel evaluates GELU through these same functions, so the row
-//         statistics of the forward pass and the values normalised later agree exactly.
+//         phi needs one hardware exp2.  Within one forward/backward pair every kernel evaluates GELU the same
+//         way - through these functions, or all of them through the table below (GaussTable) - so the row
+//         statistics of the forward pass, the values normalised later and the backward pass agree exactly.
 template <class C> struct Gauss;
 
 template <> struct Gauss<double> {
