@@ -47,12 +47,12 @@ def test_cfg3_bf16_shifted_full():
     H.check_bf16("Zsave[rows]", H.to_f64(got["Z"][idx]), ref["kept_Z"])
 
 
-def test_cfg4_bf16_headline_sampled():
-    cfg = I.CONFIGS[4]
+def sampled_check(cfg, extra_rows=()):
+    """Sampled outputs one by one, and full sums over rows through a row-sparse dY (see the module docstring)."""
     say(f"[fullsize] {cfg.name}: generating inputs")
     t = I.generate(cfg)
     rng = np.random.default_rng(4)
-    rows = np.sort(rng.choice(cfg.M, size=64, replace=False))
+    rows = np.unique(np.concatenate([rng.choice(cfg.M, size=64, replace=False), np.asarray(extra_rows, dtype=np.int64)]))
     say(f"[fullsize] {cfg.name}: HIP path, dense dY")
     got = H.run_fdl(cfg, t, check_guards=True)
     n = {k: v.numpy() for k, v in t.items()}
@@ -69,11 +69,12 @@ def test_cfg4_bf16_headline_sampled():
     H.check_bf16("dbeta", H.to_f64(got["dbeta"]), dbeta_ref)
     # anti-shortcut: outputs of the full-size run are not degenerate
     ysamp = H.to_f64(got["Y"][idx])
-    assert ysamp.std(axis=1).min() > 0.1 and ysamp.std(axis=0).min() > 0.01
+    # (a column whose gamma happens to round to zero is constant, so the column test is on all but a few)
+    assert ysamp.std(axis=1).min() > 0.1 and (ysamp.std(axis=0) > 0.01).mean() > 0.99
     del got
 
     # ---- dY supported on a sampled set of rows: the sums over rows are computable in full
-    S = np.sort(rng.choice(cfg.M, size=256, replace=False))
+    S = np.unique(np.concatenate([rng.choice(cfg.M, size=256, replace=False), np.asarray(extra_rows, dtype=np.int64)]))
     dY_sparse = torch.zeros_like(t["dY"])
     dY_sparse[torch.as_tensor(S)] = t["dY"][torch.as_tensor(S)]
     t2 = dict(t)
@@ -90,3 +91,14 @@ def test_cfg4_bf16_headline_sampled():
     mask = torch.ones(cfg.M, dtype=torch.bool, device="cuda")
     mask[idx] = False
     assert float(got["dX"][mask].float().abs().max()) == 0.0, "rows with zero upstream gradient must have dX = 0"
+
+
+def test_cfg4_bf16_headline_sampled():
+    sampled_check(I.CONFIGS[4])
+
+
+def test_tall_ragged_batch_bf16_sampled():
+    """More than 2^31 bytes per M x N tensor (64-bit offsets everywhere) and a ragged row count on the fast path:
+    partial last row tile in F1 and dX, dW as fast kernel over the first rows plus the generic kernel over the last 64."""
+    M = (1 << 20) + 64
+    sampled_check(I.custom("bf16", M, 128, 2048, seed=37), extra_rows=(0, M - 1, M - 64, M - 65, (1 << 20) - 1))
