@@ -56,7 +56,8 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   // ---- backward
   q.b1_fused = b1_fused_supported(dt, N);
   if (q.b1_fused) {
-    q.b1_groups = (int)(Mp < 512 ? Mp : 512);
+    const int64_t want = b1_fused_groups(dt, N);
+    q.b1_groups = (int)(Mp < want ? Mp : want);
     q.b1_rows_per_group = 0;
   } else {
     int64_t rpg = (Mp + 1023) / 1024;

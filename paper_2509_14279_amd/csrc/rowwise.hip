@@ -635,6 +635,17 @@ bool b1_fused_supported(int dt, int64_t N) {
   return fused_shape(N, V, V == vmax, &fs);
 }
 
+// Row groups (= workgroups) of the fused kernel.  With 1024 threads one workgroup fills a CU's register file:
+// 256 groups are then all resident at once and the rows in flight across the chip form one contiguous window
+// (measured 5 % faster than 512 groups in two batches); the smaller shapes do best with 512.
+int b1_fused_groups(int dt, int64_t N) {
+  const int vmax = dt == kF32 ? 4 : 8;
+  const int V = (N % vmax == 0) ? vmax : 1;
+  FusedShape fs;
+  if (!fused_shape(N, V, V == vmax, &fs)) return 512;
+  return fs.nt == 1024 ? 256 : 512;
+}
+
 void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, bool table, const void* dY, const void* Zsave,
                      const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart, hipStream_t s) {
   if (dt == kF32) b1_fused_impl<float, false>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
