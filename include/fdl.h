@@ -45,6 +45,9 @@
 extern "C" {
 #endif
 
+/* The library is built with hidden symbol visibility; the entry points below are its only exports. */
+#define FDL_API __attribute__((visibility("default")))
+
 typedef enum {
   FDL_OK = 0,
   FDL_ERR_NULL = 1,       /* a required pointer is NULL                           */
@@ -62,14 +65,14 @@ typedef enum {
 } fdl_dtype;
 
 /* Human-readable name of a status code (host pointer to a static string). */
-const char* fdl_status_string(fdl_status s);
+FDL_API const char* fdl_status_string(fdl_status s);
 
 /*
  * Bytes of device scratch that fdl_forward and fdl_backward need for this
  * problem (the larger of the two, so one buffer serves both).  Returns 0 for
  * an invalid dtype or shape.  Host-only: touches no device.
  */
-size_t fdl_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N);
+FDL_API size_t fdl_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N);
 
 /*
  * Forward:  Z = X W^T + b;  A = GELU_erf(Z) = Z * Phi(Z);
@@ -85,7 +88,7 @@ size_t fdl_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N);
  *      kept for backward;  mean, rstd [M] fp32 = row statistics of
  *      GELU_erf(Zsave) (i.e. of the stored, rounded pre-activation).
  */
-fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+FDL_API fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
                        const void* X, const void* W,
                        const float* b, const float* gamma, const float* beta, float eps,
                        void* Y, void* Zsave, float* mean, float* rstd,
@@ -107,7 +110,7 @@ fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
  * in : dY [M,N], X [M,K], W [N,K], Zsave [M,N] (dt);  gamma [N], mean, rstd [M] fp32.
  * out: dX [M,K], dW [N,K] (dt);  db, dgamma, dbeta [N] fp32.
  */
-fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+FDL_API fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
                         const void* dY, const void* X, const void* W, const float* gamma,
                         const void* Zsave, const float* mean, const float* rstd,
                         void* dX, void* dW, float* db, float* dgamma, float* dbeta,
@@ -123,7 +126,9 @@ fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
  * `events` is a HOST array of 2*FDL_PHASE_COUNT hipEvent_t handles created by the caller (or NULL to switch
  * the instrumentation off, the default).  While set, fdl_forward / fdl_backward record events[2*p] just
  * before and events[2*p+1] just after the launches of phase p on the call's stream.  The array is copied;
- * the events stay owned by the caller.  Process-wide state: not thread-safe, meant for benchmarks only.
+ * the events stay owned by the caller.  This is a measurement hook, not part of the operator's contract: it is
+ * process-wide state that changes what the other entry points enqueue, it is not thread-safe, and it must not be
+ * switched while another thread is inside the library.  Benchmarks only.
  * Returns FDL_ERR_SHAPE if count != 2*FDL_PHASE_COUNT (and events != NULL).
  */
 typedef enum {
@@ -132,7 +137,7 @@ typedef enum {
   FDL_PHASE_COUNT = 7
 } fdl_phase;
 
-fdl_status fdl_set_phase_events(void* const* events, int count);
+FDL_API fdl_status fdl_set_phase_events(void* const* events, int count);
 
 #ifdef __cplusplus
 }

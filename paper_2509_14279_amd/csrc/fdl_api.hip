@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <mutex>
 
 namespace fdl {
 namespace {
@@ -30,7 +31,51 @@ bool shape_ok(int64_t M, int64_t K, int64_t N) {
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+thread_local bool t_failure_noted = false;
+
 }  // namespace
+
+void note_failure(const char* what, hipError_t e) {
+  fprintf(stderr, "libfdl: %s failed: %s\n", what, hipGetErrorString(e));
+  t_failure_noted = true;
+}
+
+bool device_info(DeviceInfo* out) {
+  static std::mutex mu;
+  static DeviceInfo cache[kMaxDevices];
+  static bool have[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) { note_failure("hipGetDevice", e); return false; }
+  if (dev < 0 || dev >= kMaxDevices) { note_failure("device ordinal beyond the supported range", hipErrorInvalidDevice); return false; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (!have[dev]) {
+    int cus = 0, xcds = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || cus < 1) { note_failure("hipDeviceGetAttribute(compute units)", e); return false; }
+    // a runtime that does not know the attribute yet reports an error: every gfx950 part has 8 dies
+    if (hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev) != hipSuccess || xcds < 1) {
+      (void)hipGetLastError();
+      xcds = 8;
+    }
+    if (cus % xcds != 0) xcds = 1;
+    cache[dev].cus = cus; cache[dev].xcds = xcds;
+    have[dev] = true;
+  }
+  *out = cache[dev];
+  return true;
+}
+
+bool ensure_dynamic_lds(const void* kernel, int bytes, OnceFlags* flags) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) { note_failure("hipGetDevice", e); return false; }
+  if (flags->done[dev].load(std::memory_order_acquire)) return true;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);   // idempotent: a race is harmless
+  if (e != hipSuccess) { note_failure("hipFuncSetAttribute(dynamic LDS size)", e); return false; }
+  flags->done[dev].store(1, std::memory_order_release);
+  return true;
+}
 
 bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   if (dt != kF32 && dt != kBF16) return false;
@@ -49,7 +94,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.stat_tile_w = q.f1_fast ? fast_f1_stat_tile_w() : 16 * q.f1_wb;
   q.stat_tiles = (int)((N + q.stat_tile_w - 1) / q.stat_tile_w);
   size_t off = 0;
-  q.off_part = off; off += align256((size_t)q.stat_tiles * Mp * 8);
+  q.off_part = off; off += align256(q.f2_rows ? 0 : (size_t)q.stat_tiles * Mp * 8);   // no partials where F2 takes the statistics
   q.off_xtail = off; off += align256(q.f1_fast ? fast_f1_tail_bytes(M, K) : 0);
   q.fwd_bytes = off;
 
@@ -148,40 +193,44 @@ struct PhaseTimer {
 // The HIP "last error" is per-thread state shared with everything else the caller does on this thread (an
 // allocator that probed and recovered from an out-of-memory condition leaves it set): it is cleared on entry so
 // that only this call's launches are reported, and the reason of a failed launch goes to stderr.
-static void clear_stale_error() { (void)hipGetLastError(); }
+static void clear_stale_error() { (void)hipGetLastError(); t_failure_noted = false; }
 static fdl_status launch_status() {
   const hipError_t e = hipGetLastError();
+  if (t_failure_noted) { t_failure_noted = false; return FDL_ERR_LAUNCH; }
   if (e == hipSuccess) return FDL_OK;
   fprintf(stderr, "libfdl: kernel launch failed: %s\n", hipGetErrorString(e));
   return FDL_ERR_LAUNCH;
 }
 
-extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
-                                  const float* b, const float* gamma, const float* beta, float eps, void* Y,
-                                  void* Zsave, float* mean, float* rstd, void* workspace, size_t workspace_bytes,
-                                  void* hip_stream) {
+// Validation shared by the forward entry points (everything except the scratch buffer).
+static fdl_status check_forward_args(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
+                                     const float* b, const float* gamma, const float* beta, float eps, const void* Y,
+                                     const void* Zsave, const float* mean, const float* rstd, Plan* p) {
   if (!X || !W || !b || !gamma || !beta || !Y || !Zsave || !mean || !rstd) return FDL_ERR_NULL;
   if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
   if (!(eps >= 0.0f) || std::isinf(eps)) return FDL_ERR_EPS;
-  Plan p;
-  const fdl_status st = check_common(dt, M, K, N, workspace, workspace_bytes, &p);
-  if (st != FDL_OK) return st;
-  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(Zsave, 16) || !aligned(b, 16) ||
-      !aligned(gamma, 16) || !aligned(beta, 16) || !aligned(mean, 16) || !aligned(rstd, 16))
-    return FDL_ERR_ALIGN;
-  if (M == 0) return FDL_OK;
-  clear_stale_error();
-  hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  char* ws = static_cast<char*>(workspace);
-  void* part = ws + p.off_part;
+  if (!make_plan((int)dt, M, K, N, p)) return FDL_ERR_SHAPE;
+  return FDL_OK;
+}
+static bool forward_args_aligned(const void* X, const void* W, const float* b, const float* gamma, const float* beta,
+                                 const void* Y, const void* Zsave, const float* mean, const float* rstd) {
+  return aligned(X, 16) && aligned(W, 16) && aligned(Y, 16) && aligned(Zsave, 16) && aligned(b, 16) &&
+         aligned(gamma, 16) && aligned(beta, 16) && aligned(mean, 16) && aligned(rstd, 16);
+}
 
+// The launches of the forward pass; ws: at least p.fwd_bytes bytes of device scratch, 256-byte aligned.
+static fdl_status forward_launches(const Plan& p, const void* X, const void* W, const float* b, const float* gamma,
+                                   const float* beta, float eps, void* Y, void* Zsave, float* mean, float* rstd,
+                                   char* ws, hipStream_t s) {
+  const int64_t M = p.M, K = p.K, N = p.N;
+  void* part = ws + p.off_part;
   {
     PhaseTimer t(FDL_PHASE_F1, s);
     if (p.f1_fast) {
       launch_fast_f1(M, K, N, X, W, b, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
     } else {
       GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
-      launch_generic_f1((int)dt, g, b, Zsave, part, s);
+      launch_generic_f1(p.dt, g, b, Zsave, part, s);
     }
   }
   {
@@ -191,9 +240,25 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
   {
     PhaseTimer t(FDL_PHASE_F2, s);
     if (p.f2_rows) launch_f2_rows(M, N, eps, Zsave, gamma, beta, Y, mean, rstd, s);
-    else launch_f2((int)dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
+    else launch_f2(p.dt, M, N, Zsave, mean, rstd, gamma, beta, Y, s);
   }
   return launch_status();
+}
+
+extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
+                                  const float* b, const float* gamma, const float* beta, float eps, void* Y,
+                                  void* Zsave, float* mean, float* rstd, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  Plan p;
+  fdl_status st = check_forward_args(dt, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, &p);
+  if (st != FDL_OK) return st;
+  st = check_common(dt, M, K, N, workspace, workspace_bytes, &p);
+  if (st != FDL_OK) return st;
+  if (!forward_args_aligned(X, W, b, gamma, beta, Y, Zsave, mean, rstd)) return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  return forward_launches(p, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, static_cast<char*>(workspace),
+                          static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* dY, const void* X,

@@ -36,6 +36,9 @@ namespace fdl {
 namespace {
 
 constexpr int kTile = 256;
+// The launch plan (workspace sizes included) is host-only and must not depend on which device runs it, so the split
+// of the dW reduction is planned for the part's 256 compute units; the launch itself asks the device.
+constexpr int kPlanCUs = 256;
 constexpr int kLdsStages = 128 * 1024;           // all pipeline stages together (2 x 64 KB or 4 x 32 KB)
 constexpr int kLdsBytes = kLdsStages + 4 * 8192; // + 8 KB per wave for the output block rows = 160 KB
 
@@ -63,6 +66,7 @@ struct FastParams {
   int tiles_i, tiles_j;
   int nkt;               // reduction slices per workgroup
   int split;
+  int xcds;              // accelerator dies the workgroup ids are dealt over (1: no die-aware tile order)
 };
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -215,16 +219,19 @@ void gemm_bf16_kernel(FastParams p) {
   const int wi = wave & 1, wj = wave >> 1;
 
   // ---- persistent workgroups: one per CU, each walks several output tiles.  Workgroup ids are dealt round-robin
-  // over the 8 XCDs, so XCD x owns the logical tiles [x T/8, (x+1) T/8) and its workgroups take them in turn: the 32
-  // workgroups resident on an XCD work on 32 consecutive logical tiles (4 column tiles x 8 row tiles of one band)
-  // and share 4 P panels and 8 Q panels in that XCD's L2.
+  // over the X accelerator dies (8 on this part), so die x owns the logical tiles [x T/X, (x+1) T/X) and its
+  // workgroups take them in turn: the 32 workgroups resident on a die work on 32 consecutive logical tiles (4 column
+  // tiles x 8 row tiles of one band) and share 4 P panels and 8 Q panels in that die's L2.  The host passes X > 1
+  // only when both the tile count and the grid are multiples of it.
   const int ntiles = p.tiles_i * p.tiles_j;
   int L, Lstride, Lend;
-  if ((ntiles & 7) == 0 && (gridDim.x & 7) == 0) {
-    const int per_xcd = ntiles >> 3;
-    L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    Lstride = gridDim.x >> 3;
-    Lend = ((blockIdx.x & 7) + 1) * per_xcd;
+  if (p.xcds > 1) {
+    const int X = p.xcds;
+    const int per_xcd = ntiles / X;
+    const int xcd = (int)blockIdx.x % X, slot = (int)blockIdx.x / X;
+    L = xcd * per_xcd + slot;
+    Lstride = (int)gridDim.x / X;
+    Lend = (xcd + 1) * per_xcd;
   } else {
     L = blockIdx.x; Lstride = gridDim.x; Lend = ntiles;
   }
@@ -602,20 +609,23 @@ __global__ __launch_bounds__(256) void copy_tail_rows_kernel(const bf16_t* __res
 }
 
 template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG = false>
-void launch(const FastParams& p, hipStream_t s) {
-  static bool configured = false;   // raise the dynamic LDS limit once per kernel
+void launch(FastParams p, hipStream_t s) {
+  static OnceFlags configured;   // the dynamic LDS limit is raised once per kernel and device
   auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI, BK, NS, RAG>;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    configured = true;
-  }
-  // persistent: at most one workgroup per CU (the LDS footprint allows no more); a multiple of 8 whenever the
-  // tile count is, so that every XCD gets the same number
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kLdsBytes, &configured)) return;
+  DeviceInfo di;
+  if (!device_info(&di)) return;
+  // persistent: at most one workgroup per CU (the LDS footprint allows no more); a multiple of the die count
+  // whenever the tile count is, so that every die gets the same number
   const int ntiles = p.tiles_i * p.tiles_j;
-  int wgs = 256 / p.split;
-  if (wgs < 8) wgs = 8;
+  int wgs = di.cus / p.split;
+  if (wgs < di.xcds) wgs = di.xcds;
   if (wgs > ntiles) wgs = ntiles;
-  if ((ntiles & 7) == 0) wgs &= ~7;
+  p.xcds = 1;
+  if (di.xcds > 1 && ntiles % di.xcds == 0 && wgs >= di.xcds) {
+    wgs -= wgs % di.xcds;
+    p.xcds = di.xcds;
+  }
   const dim3 grid((unsigned)wgs, (unsigned)p.split);
   hipLaunchKernelGGL(kern, grid, dim3(256), kLdsBytes, s, p);
 }
@@ -691,7 +701,7 @@ int fast_b4_split(int64_t M, int64_t K, int64_t N) {
   const int64_t tiles = (K / kTile) * (N / kTile);
   const int64_t unit = (int64_t)kB4BK * stages_of(kB4BK);   // every part is a whole number of slice groups
   int split = 1;
-  while (tiles * split * 2 <= 256 && M % (split * 2 * unit) == 0 && M / (split * 2) >= 512) split *= 2;
+  while (tiles * split * 2 <= kPlanCUs && M % (split * 2 * unit) == 0 && M / (split * 2) >= 512) split *= 2;
   return split;   // M: the rows the fast kernel covers
 }
 

@@ -14,6 +14,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace fdl {
 
 enum DType { kF32 = 0, kBF16 = 1 };
@@ -48,6 +50,22 @@ struct Plan {
 
 // Returns false when the shape or dtype is not supported.
 bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p);
+
+// ---- per-device facts and per-call failure notes --------------------------------------------------
+// Compute units and accelerator dies (each die has its own L2) of the calling thread's current device, queried from
+// the runtime once per device.  Returns false (and leaves a note, see below) if the query fails.
+struct DeviceInfo { int cus; int xcds; };
+bool device_info(DeviceInfo* out);
+
+// A launcher that cannot launch (a failed attribute call, a failed device query) prints the reason to stderr and
+// leaves a note for the calling thread; the entry point turns a note into FDL_ERR_LAUNCH.
+void note_failure(const char* what, hipError_t e);
+
+// Raise the dynamic-LDS limit of a kernel once per device (flags: one byte per device ordinal, zero-initialised,
+// owned by the caller - one array per kernel instantiation).  Safe to call from several host threads.
+constexpr int kMaxDevices = 64;
+struct OnceFlags { std::atomic<unsigned char> done[kMaxDevices]; };
+bool ensure_dynamic_lds(const void* kernel, int bytes, OnceFlags* flags);
 
 // ---- generic MFMA GEMM: C[i][j] = sum_r A(i,r) B(j,r), any shape, any alignment -----------------
 // a_rc / b_rc: the operand is contiguous along the reduction index r (element (i,r) at A[i*ld + r]);

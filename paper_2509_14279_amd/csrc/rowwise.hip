@@ -578,12 +578,9 @@ template <int CH, bool FULL, int NT>
 void launch_f2_rows_one(int64_t wgs, hipStream_t s, int64_t M, int64_t N, float eps, const bf16_t* Z, const float* gamma,
                         const float* beta, bf16_t* Y, float* mean, float* rstd) {
   constexpr size_t kLds = (size_t)CH * 4096 + GaussTable<false>::kBytes;
-  static bool configured = false;
+  static OnceFlags configured;
   auto kern = f2_rows_kernel<CH, FULL, NT>;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
-    configured = true;
-  }
+  if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kLds, &configured)) return;
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(NT), kLds, s, M, N, eps, Z, gamma, beta, Y, mean, rstd);
 }
 
@@ -598,7 +595,9 @@ void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const fl
   // a workgroup of the widest variant fills a CU's register file; narrower rows leave room for more of them
   const int64_t per_wg = nt / 64;
   int64_t wgs = (M + per_wg - 1) / per_wg;
-  const int64_t cap = 256 * (16 / ch);
+  DeviceInfo di;
+  if (!device_info(&di)) return;
+  const int64_t cap = (int64_t)di.cus * (16 / ch);
   if (wgs > cap) wgs = cap;
 #define FDL_F2R(CHH, FULL, NTT)                                                                                    \
   launch_f2_rows_one<CHH, FULL, NTT>(wgs, s, M, N,                                                                      \

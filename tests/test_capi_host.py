@@ -22,6 +22,16 @@ def test_header_symbols_are_exported():
         assert hasattr(api._lib, name), name
 
 
+def test_nothing_but_the_declared_entry_points_is_exported():
+    """The library is built with hidden visibility: its dynamic symbol table defines the C entry points and nothing
+    of its internals (the compiler's own per-translation-unit markers aside)."""
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", api.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    names = {ln.split()[-1] for ln in out.splitlines() if ln.strip()}
+    names = {n for n in names if not n.startswith("__hip_cuid_")}
+    assert names == set(api.EXPORTS), names ^ set(api.EXPORTS)
+
+
 def test_status_strings():
     names = ["FDL_OK", "FDL_ERR_NULL", "FDL_ERR_SHAPE", "FDL_ERR_DTYPE", "FDL_ERR_EPS", "FDL_ERR_WORKSPACE",
              "FDL_ERR_ALIGN", "FDL_ERR_LAUNCH"]
