@@ -95,6 +95,25 @@ FDL_API fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * fdl_forward for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and kernels as fdl_forward, but
+ * the scratch is a fixed array of FDL_STATIC_SCRATCH_BYTES bytes inside the library's device code (one copy per
+ * GPU, held from the moment the library is loaded there until the process ends).  The call allocates and frees
+ * nothing; the first call on a GPU looks up the array's device address (a host-side query, no stream work).
+ *
+ * Limit: problems whose forward scratch exceeds the array are rejected with FDL_ERR_WORKSPACE before any device
+ * call.  The forward scratch is 8 bytes per (row, column tile) of partial row statistics - none on the bf16 path
+ * with K % 128 == 0, N % 256 == 0, N <= 8192, M >= 128, which normalises without partials - plus 512 K bytes when
+ * that path sees a ragged M.  Every call on one GPU shares that GPU's array, so two calls that overlap in time on
+ * one GPU (different streams, different host threads) race: order them on one stream or with events.
+ */
+#define FDL_STATIC_SCRATCH_BYTES (16 * 1024 * 1024)
+FDL_API fdl_status fdl_forward_static(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+                                      const void* X, const void* W,
+                                      const float* b, const float* gamma, const float* beta, float eps,
+                                      void* Y, void* Zsave, float* mean, float* rstd, void* hip_stream);
+
+/*
  * Backward, given dY [M,N] and the tensors saved by fdl_forward:
  *   Ahat_ij = (GELU_erf(Z_ij) - mean_i) * rstd_i;     g_ij = dY_ij * gamma_j;
  *   c1_i = (1/N) sum_j g_ij;    c2_i = (1/N) sum_j g_ij * Ahat_ij;

@@ -24,7 +24,9 @@ LIB_PATH = os.path.join(HERE, "libfdl.so")
 FDL_F32, FDL_BF16 = 0, 1
 FDL_OK, FDL_ERR_NULL, FDL_ERR_SHAPE, FDL_ERR_DTYPE, FDL_ERR_EPS, FDL_ERR_WORKSPACE, FDL_ERR_ALIGN, FDL_ERR_LAUNCH = range(8)
 
-EXPORTS = ("fdl_status_string", "fdl_workspace_bytes", "fdl_forward", "fdl_backward", "fdl_set_phase_events")
+EXPORTS = ("fdl_status_string", "fdl_workspace_bytes", "fdl_forward", "fdl_forward_static", "fdl_backward",
+           "fdl_set_phase_events")
+FDL_STATIC_SCRATCH_BYTES = 16 * 1024 * 1024
 FDL_PHASES = ("F1", "FS", "F2", "B1", "B2", "B3", "B4")
 
 if not os.path.exists(LIB_PATH):
@@ -42,6 +44,8 @@ def _bind(lib):
     lib.fdl_workspace_bytes.argtypes = [_int, _i64, _i64, _i64]
     lib.fdl_forward.restype = _int
     lib.fdl_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.fdl_forward_static.restype = _int
+    lib.fdl_forward_static.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp, _vp]
     lib.fdl_backward.restype = _int
     lib.fdl_backward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                  _vp, _sz, _vp]
@@ -102,6 +106,11 @@ def fdl_forward_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, r
                                 int(workspace_bytes), stream))
 
 
+def fdl_forward_static_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, stream) -> int:
+    return int(_lib.fdl_forward_static(_dtype_code(dtype), M, K, N, _ptr(X), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                                       float(eps), _ptr(Y), _ptr(Zsave), _ptr(mean), _ptr(rstd), stream))
+
+
 def fdl_backward_raw(dtype, M, K, N, dY, X, W, gamma, Zsave, mean, rstd, dX, dW, db, dgamma, dbeta,
                      workspace, workspace_bytes, stream) -> int:
     return int(_lib.fdl_backward(_dtype_code(dtype), M, K, N, _ptr(dY), _ptr(X), _ptr(W), _ptr(gamma), _ptr(Zsave),
@@ -115,6 +124,15 @@ def fdl_forward(dtype, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, workspac
     N = W.shape[0]
     st = fdl_forward_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd,
                          workspace, _nbytes(workspace), _stream(stream))
+    if st != FDL_OK:
+        raise FdlError(st)
+
+
+def fdl_forward_static(dtype, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, stream=None) -> None:
+    """fdl_forward on the library's own fixed scratch array (no workspace argument, nothing allocated)."""
+    M, K = X.shape
+    N = W.shape[0]
+    st = fdl_forward_static_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, _stream(stream))
     if st != FDL_OK:
         raise FdlError(st)
 

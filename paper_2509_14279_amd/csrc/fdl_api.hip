@@ -261,6 +261,45 @@ extern "C" fdl_status fdl_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
                           static_cast<hipStream_t>(hip_stream));
 }
 
+// ---- forward pass on the library's own scratch: no allocation, no workspace argument ----------------------------
+// The scratch lives in device memory that belongs to the loaded code object: one copy per GPU, present from the
+// moment the library is loaded on that GPU until the process ends.  In host code the array's name is only a handle;
+// its device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FDL_STATIC_SCRATCH_BYTES];
+
+static char* static_scratch_address() {
+  static std::mutex mu;
+  static char* ptr[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) { note_failure("hipGetDevice", e); return nullptr; }
+  std::lock_guard<std::mutex> lock(mu);
+  if (ptr[dev] == nullptr) {
+    void* a = nullptr;
+    e = hipGetSymbolAddress(&a, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || a == nullptr) { note_failure("hipGetSymbolAddress(static scratch)", e); return nullptr; }
+    ptr[dev] = static_cast<char*>(a);
+  }
+  return ptr[dev];
+}
+
+extern "C" fdl_status fdl_forward_static(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
+                                         const float* b, const float* gamma, const float* beta, float eps, void* Y,
+                                         void* Zsave, float* mean, float* rstd, void* hip_stream) {
+  Plan p;
+  const fdl_status st = check_forward_args(dt, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, &p);
+  if (st != FDL_OK) return st;
+  if (p.fwd_bytes > (size_t)FDL_STATIC_SCRATCH_BYTES) return FDL_ERR_WORKSPACE;   // the problem needs more than the array holds
+  if (!forward_args_aligned(X, W, b, gamma, beta, Y, Zsave, mean, rstd)) return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  char* ws = static_scratch_address();
+  if (ws == nullptr) return launch_status();
+  // every scratch location a forward pass reads has been written earlier in the same pass (partial statistics
+  // per row and column tile, the padded copy of X's last rows), so nothing has to be cleared between calls
+  return forward_launches(p, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, ws, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* dY, const void* X,
                                    const void* W, const float* gamma, const void* Zsave, const float* mean,
                                    const float* rstd, void* dX, void* dW, float* db, float* dgamma, float* dbeta,

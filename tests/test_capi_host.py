@@ -87,6 +87,28 @@ def test_forward_rejects_bad_arguments_before_any_launch():
     assert _fwd(M=0) == api.FDL_OK
 
 
+def _fwd_static(dt="f32", M=4, K=4, N=4, eps=1e-5, **over):
+    a = dict(X=P, W=P, b=P, gamma=P, beta=P, Y=P, Zsave=P, mean=P, rstd=P)
+    a.update(over)
+    return api.fdl_forward_static_raw(dt, M, K, N, a["X"], a["W"], a["b"], a["gamma"], a["beta"], eps, a["Y"],
+                                      a["Zsave"], a["mean"], a["rstd"], None)
+
+
+def test_forward_static_rejects_bad_arguments_and_oversized_problems_before_any_device_call():
+    for name in ("X", "W", "b", "gamma", "beta", "Y", "Zsave", "mean", "rstd"):
+        assert _fwd_static(**{name: 0}) == api.FDL_ERR_NULL, name
+    assert _fwd_static(dt=5) == api.FDL_ERR_DTYPE
+    assert _fwd_static(K=0) == api.FDL_ERR_SHAPE
+    assert _fwd_static(eps=float("nan")) == api.FDL_ERR_EPS
+    assert _fwd_static(X=P + 4) == api.FDL_ERR_ALIGN
+    assert _fwd_static(M=0) == api.FDL_OK
+    # partial row statistics of 8 bytes per (row, 64-column tile): 65536 rows x 128 tiles = 64 MiB > the 16 MiB array
+    assert _fwd_static(dt="f32", M=65536, K=64, N=8192) == api.FDL_ERR_WORKSPACE
+    # the headline shape normalises without partials and needs no scratch at all: accepted up to the launch, which
+    # this host-only test must not reach, so only its size is checked here
+    assert api.FDL_STATIC_SCRATCH_BYTES == 16 * 1024 * 1024
+
+
 def test_backward_rejects_bad_arguments_before_any_launch():
     for name in ("dY", "X", "W", "gamma", "Zsave", "mean", "rstd", "dX", "dW", "db", "dgamma", "dbeta"):
         assert _bwd(**{name: 0}) == api.FDL_ERR_NULL, name
