@@ -3,7 +3,9 @@
     python -m paper_2509_14279_amd.build
 
 Each .hip file under csrc/ is compiled to an object file in parallel and the
-objects are linked into paper_2509_14279_amd/libfdl.so.
+objects are linked into paper_2509_14279_amd/libfdl.so.  The micro-benchmarks that
+measure the machine's ceilings for the roofline report (csrc_ceilings/) go into
+a shared object of their own, libfdl_ceilings.so, which only bench.py loads.
 """
 from __future__ import annotations
 
@@ -16,6 +18,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfdl.so")
+CEIL_SRC = os.path.join(HERE, "csrc_ceilings", "ceilings.hip")
+CEIL_LIB = os.path.join(HERE, "libfdl_ceilings.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -56,6 +60,12 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print(f"built {LIB} from {len(srcs)} sources")
+    cmd = [HIPCC, *FLAGS, "-shared", CEIL_SRC, "-o", CEIL_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for the ceilings micro-benchmarks:\n" + r.stderr)
+    if verbose:
+        print(f"built {CEIL_LIB}")
     return LIB
 
 

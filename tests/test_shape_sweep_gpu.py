@@ -43,7 +43,11 @@ def test_shape_seed_init_grid(shape, init, dtype):
         if dtype == "bf16" and N <= 2:
             outputs = ("Y", "dbeta", "dgamma")      # LayerNorm over <= 2 elements: the rest is cancellation residue
         f32_atol = 1e-3 if N == 1 else 1e-5         # N = 1: rstd = eps^-1/2 multiplies the fp32 rounding of the mean
+        H.set_ratio_label(cfg.name)
         for k in outputs:
-            H.check(cfg.dtype, k, H.to_f64(got[k]), ref[k], f32_atol=f32_atol)
-        for k in H.OUTPUTS:
-            assert np.all(np.isfinite(H.to_f64(got[k]))), k
+            H.check(cfg.dtype, k, H.to_f64(got[k]), ref[k], f32_atol=1e-5 if k == "dbeta" else f32_atol)
+        if len(outputs) < len(H.OUTPUTS):
+            # the residues are held to the condition-aware bound: bar + 2 u_bf16 x magnitude of the cancelling terms
+            S = H.backward_term_scale(n, ref, cfg.eps)
+            for k in ("dX", "dW", "db"):
+                H.check_bf16_cancelling(k, H.to_f64(got[k]), ref[k], S[k])
