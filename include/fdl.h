@@ -135,6 +135,78 @@ FDL_API fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
                         void* dX, void* dW, float* db, float* dgamma, float* dbeta,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ----------------------------------------------------------------------------------------------------------------
+ * Forward-only variant and sibling operators built on the same kernels.  Conventions as above: device pointers
+ * owned by the caller, row-major contiguous matrices in the storage type `dt`, fp32 vectors, 16-byte aligned base
+ * pointers, work enqueued on `hip_stream`, outputs overwritten, argument checks before any device call.
+ * -------------------------------------------------------------------------------------------------------------- */
+
+/*
+ * Forward pass for inference (the paper's experiments are mostly forward kernels: section "Optimizing individual
+ * operations", task table of the robust kernel benchmark): Y as fdl_forward computes it, and nothing saved for a
+ * backward pass.  The pre-activation passes through Y itself and is normalised in place, so the workspace only
+ * holds row statistics and, where the contraction emits them, partial statistics:
+ * fdl_forward_inference_workspace_bytes bytes (0 for an invalid dtype or shape), 256-byte aligned.
+ * in : X [M,K], W [N,K] (dt);  b, gamma, beta [N] fp32;  eps >= 0.     out: Y [M,N] (dt).
+ */
+FDL_API size_t fdl_forward_inference_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N);
+FDL_API fdl_status fdl_forward_inference(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+                                         const void* X, const void* W,
+                                         const float* b, const float* gamma, const float* beta, float eps,
+                                         void* Y, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Linear + ReLU, forward and backward (appendix "Highlighted CUDA Kernels: Code": "MNIST Linear-ReLU" forward kernel
+ * and "MNIST Linear-ReLU Backward Kernel"; task definition in the appendix "Robust Kernel Benchmark").
+ *   forward :  Y = max(0, X W^T + b)
+ *   backward:  the pre-activation Z = X W^T + b is recomputed from the inputs (only inputs are saved, as in the
+ *              paper's task) and never stored;  G = dY where Z > 0, else 0 (the derivative at 0 is 0);
+ *              dX = G W [M,K];  dW = G^T X [N,K];  db_j = sum_i G_ij.
+ * in : X [M,K], W [N,K], dY [M,N] (dt);  b [N] fp32.     out: Y [M,N], dX [M,K], dW [N,K] (dt);  db [N] fp32.
+ * One workspace size serves both calls (fdl_linear_relu_workspace_bytes; 0 for an invalid dtype or shape).
+ * Where the exact pre-activation is within rounding of zero, the mask of that element is decided by the arithmetic
+ * of the contraction (fp32 accumulation for bf16 storage, fp64 for fp32 storage).
+ */
+FDL_API size_t fdl_linear_relu_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N);
+FDL_API fdl_status fdl_linear_relu_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+                                           const void* X, const void* W, const float* b, void* Y,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream);
+FDL_API fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
+                                            const void* dY, const void* X, const void* W, const float* b,
+                                            void* dX, void* dW, float* db,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * LayerNorm forward over the last dimension (appendix "Highlighted CUDA Kernels: Analysis", Layernorm: row mean and
+ * variance first, then normalise and apply the affine transform; torch semantics: biased variance, eps inside the
+ * root):  Y_ij = (A_ij - mean_i) rstd_i gamma_j + beta_j.
+ * in : A [M,N] (dt);  gamma, beta [N] fp32;  eps >= 0.     out: Y [M,N] (dt);  mean, rstd [M] fp32.
+ * A and Y must not overlap.  No workspace.
+ */
+FDL_API fdl_status fdl_layernorm_forward(fdl_dtype dt, int64_t M, int64_t N,
+                                         const void* A, const float* gamma, const float* beta, float eps,
+                                         void* Y, float* mean, float* rstd, void* hip_stream);
+
+/*
+ * RMSNorm forward over the last dimension ("Llama RMSNorm Forward Kernel" listing):
+ *   Y_ij = A_ij (mean_j A_ij^2 + eps)^(-1/2) weight_j.
+ * in : A [M,N] (dt);  weight [N] fp32;  eps >= 0.     out: Y [M,N] (dt).  A and Y must not overlap.  No workspace.
+ */
+FDL_API fdl_status fdl_rmsnorm_forward(fdl_dtype dt, int64_t M, int64_t N,
+                                       const void* A, const float* weight, float eps, void* Y, void* hip_stream);
+
+/*
+ * Llama feed-forward block, forward (task table of the robust kernel benchmark, Llama Feedforward; appendix
+ * "Highlighted CUDA Kernels: Analysis", LlamaFFW: three matrix products and a fused SiLU-multiply, no biases):
+ *   Y = ( SiLU(X Wg^T) * (X Wu^T) ) Wd^T,     SiLU(z) = z / (1 + exp(-z)).
+ * in : X [M,D], Wg, Wu [H,D], Wd [D,H] (dt).     out: Y [M,D] (dt).
+ * Workspace: fdl_llama_ffn_workspace_bytes bytes (the two M x H intermediates; 0 for an invalid dtype or shape).
+ */
+FDL_API size_t fdl_llama_ffn_workspace_bytes(fdl_dtype dt, int64_t M, int64_t D, int64_t H);
+FDL_API fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, int64_t H,
+                                         const void* X, const void* Wg, const void* Wu, const void* Wd, void* Y,
+                                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /*
  * Optional timing instrumentation (measurement protocol: the paper times kernels with warm-up runs
  * followed by many timed runs, appendix "Kernel Evaluation Environment"; this hook lets a harness time

@@ -25,7 +25,9 @@ FDL_F32, FDL_BF16 = 0, 1
 FDL_OK, FDL_ERR_NULL, FDL_ERR_SHAPE, FDL_ERR_DTYPE, FDL_ERR_EPS, FDL_ERR_WORKSPACE, FDL_ERR_ALIGN, FDL_ERR_LAUNCH = range(8)
 
 EXPORTS = ("fdl_status_string", "fdl_workspace_bytes", "fdl_forward", "fdl_forward_static", "fdl_backward",
-           "fdl_set_phase_events")
+           "fdl_set_phase_events", "fdl_forward_inference_workspace_bytes", "fdl_forward_inference",
+           "fdl_linear_relu_workspace_bytes", "fdl_linear_relu_forward", "fdl_linear_relu_backward",
+           "fdl_layernorm_forward", "fdl_rmsnorm_forward", "fdl_llama_ffn_workspace_bytes", "fdl_llama_ffn_forward")
 FDL_STATIC_SCRATCH_BYTES = 16 * 1024 * 1024
 FDL_PHASES = ("F1", "FS", "F2", "B1", "B2", "B3", "B4")
 
@@ -51,6 +53,21 @@ def _bind(lib):
                                  _vp, _sz, _vp]
     lib.fdl_set_phase_events.restype = _int
     lib.fdl_set_phase_events.argtypes = [ctypes.POINTER(_vp), _int]
+    for name in ("fdl_forward_inference_workspace_bytes", "fdl_linear_relu_workspace_bytes", "fdl_llama_ffn_workspace_bytes"):
+        getattr(lib, name).restype = _sz
+        getattr(lib, name).argtypes = [_int, _i64, _i64, _i64]
+    lib.fdl_forward_inference.restype = _int
+    lib.fdl_forward_inference.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _f32, _vp, _vp, _sz, _vp]
+    lib.fdl_linear_relu_forward.restype = _int
+    lib.fdl_linear_relu_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.fdl_linear_relu_backward.restype = _int
+    lib.fdl_linear_relu_backward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+    lib.fdl_layernorm_forward.restype = _int
+    lib.fdl_layernorm_forward.argtypes = [_int, _i64, _i64, _vp, _vp, _vp, _f32, _vp, _vp, _vp, _vp]
+    lib.fdl_rmsnorm_forward.restype = _int
+    lib.fdl_rmsnorm_forward.argtypes = [_int, _i64, _i64, _vp, _vp, _f32, _vp, _vp]
+    lib.fdl_llama_ffn_forward.restype = _int
+    lib.fdl_llama_ffn_forward.argtypes = [_int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
     return lib
 
 
@@ -156,3 +173,84 @@ def fdl_set_phase_events(events) -> None:
         st = _lib.fdl_set_phase_events(arr, len(events))
     if st != FDL_OK:
         raise FdlError(st)
+
+
+# ---------------------------------------------------------------- forward-only variant and sibling operators
+def _check(st: int) -> None:
+    if st != FDL_OK:
+        raise FdlError(st)
+
+
+def fdl_forward_inference_workspace_bytes(dtype, M: int, K: int, N: int) -> int:
+    return int(_lib.fdl_forward_inference_workspace_bytes(_dtype_code(dtype), M, K, N))
+
+
+def fdl_forward_inference_raw(dtype, M, K, N, X, W, b, gamma, beta, eps, Y, workspace, workspace_bytes, stream) -> int:
+    return int(_lib.fdl_forward_inference(_dtype_code(dtype), M, K, N, _ptr(X), _ptr(W), _ptr(b), _ptr(gamma), _ptr(beta),
+                                          float(eps), _ptr(Y), _ptr(workspace), int(workspace_bytes), stream))
+
+
+def fdl_forward_inference(dtype, X, W, b, gamma, beta, eps, Y, workspace, stream=None) -> None:
+    """Y = LayerNorm(GELU(X W^T + b)) gamma + beta, nothing saved for backward."""
+    M, K = X.shape
+    _check(fdl_forward_inference_raw(dtype, M, K, W.shape[0], X, W, b, gamma, beta, eps, Y, workspace, _nbytes(workspace),
+                                     _stream(stream)))
+
+
+def fdl_linear_relu_workspace_bytes(dtype, M: int, K: int, N: int) -> int:
+    return int(_lib.fdl_linear_relu_workspace_bytes(_dtype_code(dtype), M, K, N))
+
+
+def fdl_linear_relu_forward_raw(dtype, M, K, N, X, W, b, Y, workspace, workspace_bytes, stream) -> int:
+    return int(_lib.fdl_linear_relu_forward(_dtype_code(dtype), M, K, N, _ptr(X), _ptr(W), _ptr(b), _ptr(Y), _ptr(workspace),
+                                            int(workspace_bytes), stream))
+
+
+def fdl_linear_relu_forward(dtype, X, W, b, Y, workspace, stream=None) -> None:
+    M, K = X.shape
+    _check(fdl_linear_relu_forward_raw(dtype, M, K, W.shape[0], X, W, b, Y, workspace, _nbytes(workspace), _stream(stream)))
+
+
+def fdl_linear_relu_backward_raw(dtype, M, K, N, dY, X, W, b, dX, dW, db, workspace, workspace_bytes, stream) -> int:
+    return int(_lib.fdl_linear_relu_backward(_dtype_code(dtype), M, K, N, _ptr(dY), _ptr(X), _ptr(W), _ptr(b), _ptr(dX),
+                                             _ptr(dW), _ptr(db), _ptr(workspace), int(workspace_bytes), stream))
+
+
+def fdl_linear_relu_backward(dtype, dY, X, W, b, dX, dW, db, workspace, stream=None) -> None:
+    M, K = X.shape
+    _check(fdl_linear_relu_backward_raw(dtype, M, K, W.shape[0], dY, X, W, b, dX, dW, db, workspace, _nbytes(workspace),
+                                        _stream(stream)))
+
+
+def fdl_layernorm_forward_raw(dtype, M, N, A, gamma, beta, eps, Y, mean, rstd, stream) -> int:
+    return int(_lib.fdl_layernorm_forward(_dtype_code(dtype), M, N, _ptr(A), _ptr(gamma), _ptr(beta), float(eps), _ptr(Y),
+                                          _ptr(mean), _ptr(rstd), stream))
+
+
+def fdl_layernorm_forward(dtype, A, gamma, beta, eps, Y, mean, rstd, stream=None) -> None:
+    M, N = A.shape
+    _check(fdl_layernorm_forward_raw(dtype, M, N, A, gamma, beta, eps, Y, mean, rstd, _stream(stream)))
+
+
+def fdl_rmsnorm_forward_raw(dtype, M, N, A, weight, eps, Y, stream) -> int:
+    return int(_lib.fdl_rmsnorm_forward(_dtype_code(dtype), M, N, _ptr(A), _ptr(weight), float(eps), _ptr(Y), stream))
+
+
+def fdl_rmsnorm_forward(dtype, A, weight, eps, Y, stream=None) -> None:
+    M, N = A.shape
+    _check(fdl_rmsnorm_forward_raw(dtype, M, N, A, weight, eps, Y, _stream(stream)))
+
+
+def fdl_llama_ffn_workspace_bytes(dtype, M: int, D: int, H: int) -> int:
+    return int(_lib.fdl_llama_ffn_workspace_bytes(_dtype_code(dtype), M, D, H))
+
+
+def fdl_llama_ffn_forward_raw(dtype, M, D, H, X, Wg, Wu, Wd, Y, workspace, workspace_bytes, stream) -> int:
+    return int(_lib.fdl_llama_ffn_forward(_dtype_code(dtype), M, D, H, _ptr(X), _ptr(Wg), _ptr(Wu), _ptr(Wd), _ptr(Y),
+                                          _ptr(workspace), int(workspace_bytes), stream))
+
+
+def fdl_llama_ffn_forward(dtype, X, Wg, Wu, Wd, Y, workspace, stream=None) -> None:
+    M, D = X.shape
+    _check(fdl_llama_ffn_forward_raw(dtype, M, D, Wg.shape[0], X, Wg, Wu, Wd, Y, workspace, _nbytes(workspace),
+                                     _stream(stream)))

@@ -377,3 +377,267 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   }
   return launch_status();
 }
+
+
+// =====================================================================================================================
+// Forward-only variant and the sibling operators on the same kernels
+// =====================================================================================================================
+
+// ---- forward for inference: nothing is saved for a backward pass ---------------------------------------------------
+// The pre-activation is written into Y and normalised there (the normalisation reads an element before it writes it),
+// so no M x N scratch is needed: the workspace holds the row statistics, the partial statistics where the GEMM
+// epilogue emits them, and the padded copy of X's last rows.
+namespace {
+struct InferencePlan { Plan p; size_t off_mean, off_rstd, bytes; };
+bool make_inference_plan(int dt, int64_t M, int64_t K, int64_t N, InferencePlan* q) {
+  if (!make_plan(dt, M, K, N, &q->p)) return false;
+  const int64_t Mp = M > 0 ? M : 1;
+  size_t off = q->p.fwd_bytes;
+  q->off_mean = off; off += align256((size_t)Mp * 4);
+  q->off_rstd = off; off += align256((size_t)Mp * 4);
+  q->bytes = off;
+  return true;
+}
+}  // namespace
+
+extern "C" size_t fdl_forward_inference_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N) {
+  InferencePlan q;
+  if (!make_inference_plan((int)dt, M, K, N, &q)) return 0;
+  return q.bytes;
+}
+
+extern "C" fdl_status fdl_forward_inference(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
+                                            const float* b, const float* gamma, const float* beta, float eps, void* Y,
+                                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!X || !W || !b || !gamma || !beta || !Y) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return FDL_ERR_EPS;
+  InferencePlan q;
+  if (!make_inference_plan((int)dt, M, K, N, &q)) return FDL_ERR_SHAPE;
+  if (workspace == nullptr || workspace_bytes < q.bytes) return FDL_ERR_WORKSPACE;
+  if (!aligned(workspace, 256)) return FDL_ERR_ALIGN;
+  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(b, 16) || !aligned(gamma, 16) || !aligned(beta, 16))
+    return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  char* ws = static_cast<char*>(workspace);
+  return forward_launches(q.p, X, W, b, gamma, beta, eps, Y, /*Zsave=*/Y, reinterpret_cast<float*>(ws + q.off_mean),
+                          reinterpret_cast<float*>(ws + q.off_rstd), ws, static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- Linear + ReLU -------------------------------------------------------------------------------------------------
+namespace {
+// Workspace of the Linear+ReLU pair (one layout for both passes): the masked upstream gradient G [M][N] in the
+// storage type with rows padded to whole tiles (the fast dX kernel reads whole tiles), the first-stage column
+// partials of db, the fp32 partial sums of a split dW reduction, and the padded copy of X's last rows.
+struct ReluPlan { Plan p; size_t off_g, off_colpart, off_dwpart, off_xtail, bytes; };
+bool make_relu_plan(int dt, int64_t M, int64_t K, int64_t N, ReluPlan* q) {
+  if (!make_plan(dt, M, K, N, &q->p)) return false;
+  const Plan& p = q->p;
+  const size_t ts = dt == kF32 ? 4 : 2, cs = dt == kF32 ? 8 : 4;
+  const int64_t Mp = M > 0 ? M : 1;
+  const int b4_parts = p.b4_split + (p.b4_fast && p.b4_fast_rows < M ? 1 : 0);
+  size_t off = 0;
+  q->off_g = off; off += align256((size_t)((Mp + 255) / 256 * 256) * N * ts);
+  q->off_colpart = off; off += align256((size_t)colsum_groups(Mp) * N * cs);
+  q->off_dwpart = off; off += align256(b4_parts > 1 ? (size_t)b4_parts * N * K * 4 : 0);
+  q->off_xtail = off; off += align256(p.f1_fast ? fast_f1_tail_bytes(M, K) : 0);
+  q->bytes = off;
+  return true;
+}
+fdl_status check_ws(const void* workspace, size_t have, size_t need) {
+  if (workspace == nullptr || have < need) return FDL_ERR_WORKSPACE;
+  if (!aligned(workspace, 256)) return FDL_ERR_ALIGN;
+  return FDL_OK;
+}
+}  // namespace
+
+extern "C" size_t fdl_linear_relu_workspace_bytes(fdl_dtype dt, int64_t M, int64_t K, int64_t N) {
+  ReluPlan q;
+  if (!make_relu_plan((int)dt, M, K, N, &q)) return 0;
+  return q.bytes;
+}
+
+extern "C" fdl_status fdl_linear_relu_forward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* X, const void* W,
+                                              const float* b, void* Y, void* workspace, size_t workspace_bytes,
+                                              void* hip_stream) {
+  if (!X || !W || !b || !Y) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  ReluPlan q;
+  if (!make_relu_plan((int)dt, M, K, N, &q)) return FDL_ERR_SHAPE;
+  const fdl_status st = check_ws(workspace, workspace_bytes, q.bytes);
+  if (st != FDL_OK) return st;
+  if (!aligned(X, 16) || !aligned(W, 16) || !aligned(Y, 16) || !aligned(b, 16)) return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  if (q.p.f1_fast) {
+    launch_fast_xwt(1, M, K, N, X, false, W, b, nullptr, Y, ws + q.off_xtail, s);
+  } else {
+    GemmDesc g = {X, W, M, N, K, K, K, true, true, q.p.f1_wb};
+    launch_generic_xwt((int)dt, 1, g, b, nullptr, Y, s);
+  }
+  return launch_status();
+}
+
+extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N, const void* dY, const void* X,
+                                               const void* W, const float* b, void* dX, void* dW, float* db,
+                                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!dY || !X || !W || !b || !dX || !dW || !db) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  ReluPlan q;
+  if (!make_relu_plan((int)dt, M, K, N, &q)) return FDL_ERR_SHAPE;
+  const fdl_status st = check_ws(workspace, workspace_bytes, q.bytes);
+  if (st != FDL_OK) return st;
+  if (!aligned(dY, 16) || !aligned(X, 16) || !aligned(W, 16) || !aligned(b, 16) || !aligned(dX, 16) || !aligned(dW, 16) ||
+      !aligned(db, 16))
+    return FDL_ERR_ALIGN;
+  clear_stale_error();
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const Plan& p = q.p;
+  if (M == 0) {
+    const int64_t nk = N * K;
+    if (dt == FDL_F32) hipLaunchKernelGGL(zero_f32_kernel, dim3(256), dim3(256), 0, s, (float*)dW, nk);
+    else hipLaunchKernelGGL(zero_u16_kernel, dim3(256), dim3(256), 0, s, (unsigned short*)dW, nk);
+    hipLaunchKernelGGL(zero_f32_kernel, dim3(8), dim3(256), 0, s, db, N);
+    return launch_status();
+  }
+  char* ws = static_cast<char*>(workspace);
+  void* G = ws + q.off_g;
+  void* colpart = ws + q.off_colpart;
+  // G = dY where X W^T + b > 0: the pre-activation is recomputed and never stored
+  if (p.f1_fast) {
+    launch_fast_xwt(2, M, K, N, X, false, W, b, dY, G, ws + q.off_xtail, s);
+  } else {
+    GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
+    launch_generic_xwt((int)dt, 2, g, b, dY, G, s);
+  }
+  launch_colsum((int)dt, M, N, G, colpart, db, s);
+  if (p.b3_fast) {
+    launch_fast_b3(M, K, N, G, W, dX, s);
+  } else {
+    GemmDesc g = {G, W, M, K, N, N, K, true, false, p.b3_wb};
+    launch_generic_store((int)dt, g, dX, s);
+  }
+  if (p.b4_fast) {
+    const int64_t Mf = p.b4_fast_rows;
+    const int extra = Mf < M ? 1 : 0;
+    float* dwpart = reinterpret_cast<float*>(ws + q.off_dwpart);
+    launch_fast_b4(Mf, K, N, p.b4_split, extra, G, X, dW, dwpart, s);
+    if (extra) {
+      const char* Gt = static_cast<const char*>(G) + (size_t)Mf * N * 2;
+      const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
+      GemmDesc g = {Gt, Xt, N, K, M - Mf, N, K, false, false, p.b4_wb};
+      launch_generic_store_f32(g, dwpart + (size_t)p.b4_split * N * K, s);
+      launch_fast_b4_reduce(K, N, p.b4_split + 1, dwpart, dW, s);
+    }
+  } else {
+    GemmDesc g = {G, X, N, K, M, N, K, false, false, p.b4_wb};
+    launch_generic_store((int)dt, g, dW, s);
+  }
+  return launch_status();
+}
+
+// ---- LayerNorm and RMSNorm forward ---------------------------------------------------------------------------------
+static bool norm_shape_ok(int64_t M, int64_t N) {
+  return M >= 0 && N >= 1 && M <= kMaxDim && N <= kMaxDim && M * N <= kMaxElems;
+}
+
+extern "C" fdl_status fdl_layernorm_forward(fdl_dtype dt, int64_t M, int64_t N, const void* A, const float* gamma,
+                                            const float* beta, float eps, void* Y, float* mean, float* rstd,
+                                            void* hip_stream) {
+  if (!A || !gamma || !beta || !Y || !mean || !rstd) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return FDL_ERR_EPS;
+  if (!norm_shape_ok(M, N)) return FDL_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(Y, 16) || !aligned(gamma, 16) || !aligned(beta, 16) || !aligned(mean, 16) || !aligned(rstd, 16))
+    return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  launch_layernorm((int)dt, M, N, eps, A, gamma, beta, Y, mean, rstd, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+extern "C" fdl_status fdl_rmsnorm_forward(fdl_dtype dt, int64_t M, int64_t N, const void* A, const float* weight, float eps,
+                                          void* Y, void* hip_stream) {
+  if (!A || !weight || !Y) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  if (!(eps >= 0.0f) || std::isinf(eps)) return FDL_ERR_EPS;
+  if (!norm_shape_ok(M, N)) return FDL_ERR_SHAPE;
+  if (!aligned(A, 16) || !aligned(Y, 16) || !aligned(weight, 16)) return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  launch_rmsnorm((int)dt, M, N, eps, A, weight, Y, static_cast<hipStream_t>(hip_stream));
+  return launch_status();
+}
+
+// ---- Llama feed-forward block, forward -----------------------------------------------------------------------------
+namespace {
+// Workspace: G and U [Mpad][H] in the storage type (the activation overwrites G; rows padded to whole tiles so that the
+// down projection's fast kernel may read a partial last row tile), then the padded copy of X's last rows.
+struct FfnPlan {
+  int up_fast, down_fast, up_wb, down_wb;
+  size_t off_g, off_u, off_xtail, bytes;
+};
+bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
+  if (dt != kF32 && dt != kBF16) return false;
+  if (M < 0 || D < 1 || H < 1 || M > kMaxDim || D > kMaxDim || H > kMaxDim) return false;
+  if (M * H > kMaxElems || M * D > kMaxElems || H * D > kMaxElems) return false;
+  const size_t ts = dt == kF32 ? 4 : 2;
+  const int64_t Mp = M > 0 ? M : 1;
+  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  q->up_fast = dt == kBF16 && fast_f1_supported(M, D, H);      // [M,D] x [H,D]^T
+  q->down_fast = dt == kBF16 && fast_f1_supported(M, H, D);    // [M,H] x [D,H]^T
+  q->up_wb = pick_wb(Mp, H);
+  q->down_wb = pick_wb(Mp, D);
+  size_t off = 0;
+  const size_t mh = align256((size_t)((Mp + 255) / 256 * 256) * H * ts);
+  q->off_g = off; off += mh;
+  q->off_u = off; off += mh;
+  q->off_xtail = off; off += align256(q->up_fast ? fast_f1_tail_bytes(M, D) : 0);
+  q->bytes = off;
+  return true;
+}
+}  // namespace
+
+extern "C" size_t fdl_llama_ffn_workspace_bytes(fdl_dtype dt, int64_t M, int64_t D, int64_t H) {
+  FfnPlan q;
+  if (!make_ffn_plan((int)dt, M, D, H, &q)) return 0;
+  return q.bytes;
+}
+
+extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, int64_t H, const void* X, const void* Wg,
+                                            const void* Wu, const void* Wd, void* Y, void* workspace,
+                                            size_t workspace_bytes, void* hip_stream) {
+  if (!X || !Wg || !Wu || !Wd || !Y) return FDL_ERR_NULL;
+  if (dt != FDL_F32 && dt != FDL_BF16) return FDL_ERR_DTYPE;
+  FfnPlan q;
+  if (!make_ffn_plan((int)dt, M, D, H, &q)) return FDL_ERR_SHAPE;
+  const fdl_status st = check_ws(workspace, workspace_bytes, q.bytes);
+  if (st != FDL_OK) return st;
+  if (!aligned(X, 16) || !aligned(Wg, 16) || !aligned(Wu, 16) || !aligned(Wd, 16) || !aligned(Y, 16)) return FDL_ERR_ALIGN;
+  if (M == 0) return FDL_OK;
+  clear_stale_error();
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(workspace);
+  void* G = ws + q.off_g;
+  void* U = ws + q.off_u;
+  if (q.up_fast) {
+    launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, G, ws + q.off_xtail, s);
+    launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, U, ws + q.off_xtail, s);
+  } else {
+    GemmDesc g = {X, Wg, M, H, D, D, D, true, true, q.up_wb};
+    launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, G, s);
+    g.B = Wu;
+    launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, U, s);
+  }
+  launch_silu_mul((int)dt, M * H, G, U, G, s);
+  if (q.down_fast) {
+    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, nullptr, nullptr, Y, nullptr, s);
+  } else {
+    GemmDesc g = {G, Wd, M, D, H, H, H, true, true, q.down_wb};
+    launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, Y, s);
+  }
+  return launch_status();
+}

@@ -7,6 +7,9 @@
 // the forward pass takes them here) is a sum inside the lane plus one cross-half exchange.
 //
 //   F1  Z[m][n]  = sum_k X[m][k] W[n][k] + b[n]   P = W (i = n, r-contiguous)   Q = X  (j = m, r-contiguous)
+//       (also the forward product of the sibling operators: Linear+ReLU, its backward pass's recomputation of the
+//        pre-activation with the activation mask applied to the upstream gradient, and the three products of the
+//        gated feed-forward block)
 //   B3  dX[m][k] = sum_n dZ[m][n] W[n][k]         P = W (i = k, r = n major)    Q = dZ (j = m, r-contiguous)
 //   B4  dW[n][k] = sum_m dZ[m][n] X[m][k]         P = X (i = k, r = m major)    Q = dZ (j = n, r = m major)
 // (the linear layer's forward, grad-input and grad-weight products of the paper's linear tasks.)
@@ -57,7 +60,10 @@ template <int BK> struct Geo {
   static constexpr int kWaveBytes = kOperandBytes / 4;    // each wave fills a quarter of an operand tile
 };
 
-enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2, EPI_PARTIAL = 3 };
+// EPI_STORE: C = acc.  EPI_BIAS: C = acc + bias.  EPI_F1: EPI_BIAS plus GELU and partial row statistics.
+// EPI_PARTIAL: fp32 partial sums of a split reduction.  EPI_RELU: C = max(acc + bias, 0).
+// EPI_MASK: C = aux where acc + bias > 0, else 0 (aux [J][I]: the upstream gradient of a ReLU).
+enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2, EPI_PARTIAL = 3, EPI_RELU = 4, EPI_MASK = 5 };
 
 struct FastParams {
   const bf16_t* P; const bf16_t* Q;
@@ -66,7 +72,8 @@ struct FastParams {
   int64_t ldp, ldq;
   bf16_t* C;             // [J][I]
   float* Cpart;          // [split][J][I] fp32 (split > 1)
-  const float* bias;     // [I]   (EPI_F1, EPI_BIAS)
+  const float* bias;     // [I]   (EPI_F1, EPI_BIAS, EPI_RELU, EPI_MASK)
+  const bf16_t* aux;     // [J][I] (EPI_MASK)
   f32x2* part;           // [I/128][J]  (EPI_F1)
   int I, J;              // J: valid output rows (RAG: any number >= 1; otherwise a multiple of 256)
   int tiles_i, tiles_j;
@@ -301,7 +308,7 @@ void gemm_bf16_kernel(FastParams p) {
   // values are fetched at the top of the tile by two direct loads into its output staging area, which is idle
   // until the epilogue: like every direct load they are older than the slice loads issued after them, so the main
   // loop's own waits cover them, and no register or compiler-inserted wait is involved.
-  constexpr bool kBias = EPI == EPI_BIAS || EPI == EPI_F1;
+  constexpr bool kBias = EPI == EPI_BIAS || EPI == EPI_F1 || EPI == EPI_RELU || EPI == EPI_MASK;
 
   for (;;) {
     // slice 0 of this tile has landed in stage 0 (initial fill, or prefetched during the previous tile and
@@ -498,9 +505,24 @@ void gemm_bf16_kernel(FastParams p) {
         const u32x4 v = *(const lds_u32x4*)(wtile + roff[it & 3] + (it >> 2) * 4096);
         u32x4* dst = reinterpret_cast<u32x4*>(cbase + (int64_t)(it * 4) * p.I * 2 + svoff);
         if (RAG && j0 + wj * 128 + b * 32 + it * 4 + e_rq >= p.J) continue;   // a row past the end
+        if (EPI == EPI_MASK) {
+          // v: 8 pre-activations as bf16.  The upstream gradient passes where the pre-activation is positive (bits
+          // 0x0001 .. 0x7fff: sign clear, magnitude non-zero) and is zero elsewhere.
+          const char* abase = reinterpret_cast<const char*>(p.aux + (int64_t)(j0 + wj * 128 + b * 32) * p.I + i0 + wi * 128);
+          const u32x4 d = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(abase + (int64_t)(it * 4) * p.I * 2 + svoff));
+          u32x4 g;
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const uint32_t lo = ((v[e] & 0xffffu) - 1u) < 0x7fffu ? 0x0000ffffu : 0u;
+            const uint32_t hi = ((v[e] >> 16) - 1u) < 0x7fffu ? 0xffff0000u : 0u;
+            g[e] = d[e] & (lo | hi);
+          }
+          *dst = g;
+          continue;
+        }
         // the forward output (Zsave, far larger than the caches) is streamed past them so that it does not evict
         // the operand panels the XCD's workgroups share; the smaller gradient outputs gain nothing from that
-        if (kBias) __builtin_nontemporal_store(v, dst);
+        if (kBias && EPI != EPI_MASK) __builtin_nontemporal_store(v, dst);
         else *dst = v;
       }
     };
@@ -533,7 +555,8 @@ void gemm_bf16_kernel(FastParams p) {
           for (int g = 0; g < 4; g++) {
             bf16x4 v;
 #pragma unroll
-            for (int e = 0; e < 4; e++) v[e] = (bf16_t)acc[a][b][g * 4 + e];
+            for (int e = 0; e < 4; e++)
+              v[e] = (bf16_t)(EPI == EPI_RELU ? __builtin_fmaxf(acc[a][b][g * 4 + e], 0.0f) : acc[a][b][g * 4 + e]);
             *(lds_bf16x4*)(wtile + woff[a][g]) = v;
           }
         flush_rows(b);
@@ -689,6 +712,37 @@ void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* 
     if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
     else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK)>(p, s);
   }
+}
+
+// out[m][n] = f(sum_k X[m][k] W[n][k] + bias[n]) for the sibling operators; same shape rules as launch_fast_f1.
+//   kind 0: plain product (bias may be null: then none is added)      kind 1: max(. , 0)
+//   kind 2: aux[m][n] where the sum is positive, else 0
+// xtail: fast_f1_tail_bytes(M, K) bytes of scratch when M is not a multiple of 256, unless X itself has readable rows
+// up to the next multiple of 256 (x_padded).
+void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
+                     const float* bias, const void* aux, void* out, void* xtail, hipStream_t s) {
+  FastParams p = {};
+  p.P = (const bf16_t*)W; p.Q = (const bf16_t*)X; p.ldp = K; p.ldq = K;
+  p.C = (bf16_t*)out; p.bias = bias; p.aux = (const bf16_t*)aux;
+  p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
+  p.nkt = (int)(K / kF1BK); p.split = 1;
+  const bool rag = M % kTile != 0;
+  if (rag && !x_padded) {
+    p.Qtail = (const bf16_t*)xtail;
+    hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, K,
+                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail);
+  }
+  constexpr int NS = stages_of(kF1BK);
+#define FDL_XWT(EPI)                                                              \
+  do {                                                                            \
+    if (rag) launch<false, false, EPI, kF1BK, NS, true>(p, s);                    \
+    else launch<false, false, EPI, kF1BK, NS, false>(p, s);                       \
+  } while (0)
+  if (kind == 1) FDL_XWT(EPI_RELU);
+  else if (kind == 2) FDL_XWT(EPI_MASK);
+  else if (bias != nullptr) FDL_XWT(EPI_BIAS);
+  else FDL_XWT(EPI_STORE);
+#undef FDL_XWT
 }
 
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s) {

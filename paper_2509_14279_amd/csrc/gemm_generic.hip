@@ -25,11 +25,14 @@
 namespace fdl {
 namespace {
 
-enum { EPI_STORE = 0, EPI_F1 = 1, EPI_STORE_F32 = 2 };
+// EPI_STORE: C = acc (+ bias[j] when given).  EPI_F1: bias, GELU and partial row statistics.  EPI_STORE_F32: fp32 C.
+// EPI_RELU: C = max(acc + bias[j], 0).  EPI_MASK: C = aux[i][j] where acc + bias[j] > 0, else 0.
+enum { EPI_STORE = 0, EPI_F1 = 1, EPI_STORE_F32 = 2, EPI_RELU = 3, EPI_MASK = 4 };
 
 struct GemmParams {
   const void* A; const void* B; void* C;
   const float* bias; f32x2* part;
+  const void* aux;       // [I][J] in the storage type (EPI_MASK)
   int64_t I, J, R, lda, ldb;
   int a_vec, b_vec;
 };
@@ -211,7 +214,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
           if (i < p.I && j < p.J) Cf[i * p.J + j] = (float)acc[a][b][r];
         }
       }
-  } else if (EPI == EPI_STORE) {
+  } else if (EPI == EPI_STORE || EPI == EPI_RELU || EPI == EPI_MASK) {
+    AccT bias[WB];
+#pragma unroll
+    for (int b = 0; b < WB; b++) {
+      const int64_t j = jw + b * 16 + l16;
+      bias[b] = (p.bias != nullptr && j < p.J) ? (AccT)p.bias[j] : (AccT)0;
+    }
+    const T* aux = static_cast<const T*>(p.aux);
 #pragma unroll
     for (int a = 0; a < WB; a++)
 #pragma unroll
@@ -220,7 +230,12 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
 #pragma unroll
         for (int b = 0; b < WB; b++) {
           const int64_t j = jw + b * 16 + l16;
-          if (i < p.I && j < p.J) C[i * p.J + j] = to_storage<T, AccT>(acc[a][b][r]);
+          if (i < p.I && j < p.J) {
+            const AccT z = acc[a][b][r] + bias[b];
+            if (EPI == EPI_MASK) C[i * p.J + j] = z > (AccT)0 ? aux[i * p.J + j] : (T)0.0f;
+            else if (EPI == EPI_RELU) C[i * p.J + j] = to_storage<T, AccT>(z > (AccT)0 ? z : (AccT)0);
+            else C[i * p.J + j] = to_storage<T, AccT>(z);
+          }
         }
       }
   } else {
@@ -299,7 +314,7 @@ template <class T, int EPI> void dispatch(const GemmDesc& g, GemmParams p, hipSt
 
 GemmParams base_params(const GemmDesc& g) {
   GemmParams p;
-  p.A = g.A; p.B = g.B; p.C = nullptr; p.bias = nullptr; p.part = nullptr;
+  p.A = g.A; p.B = g.B; p.C = nullptr; p.bias = nullptr; p.part = nullptr; p.aux = nullptr;
   p.I = g.I; p.J = g.J; p.R = g.R; p.lda = g.lda; p.ldb = g.ldb; p.a_vec = 0; p.b_vec = 0;
   return p;
 }
@@ -320,6 +335,24 @@ void launch_generic_store_f32(const GemmDesc& g, float* C, hipStream_t s) {
   p.b_vec = ((uintptr_t)g.B % 8 == 0) && (g.ldb % 4 == 0);
   if (g.wb == 4) launch_one<bf16_t, false, false, 4, EPI_STORE_F32>(p, s);
   else launch_one<bf16_t, false, false, 2, EPI_STORE_F32>(p, s);
+}
+
+// C[i][j] = f(sum_r A(i,r) B(j,r) + bias[j]), both operands reduction-contiguous (the forward product's orientation):
+// kind 0 plain (bias may be null), 1 max(., 0), 2 aux[i][j] where the sum is positive else 0
+void launch_generic_xwt(int dt, int kind, const GemmDesc& g, const float* bias, const void* aux, void* C, hipStream_t s) {
+  GemmParams p = base_params(g);
+  p.C = C; p.bias = bias; p.aux = aux;
+  const size_t es = dt == kF32 ? 4 : 2;
+  p.a_vec = ((uintptr_t)g.A % (4 * es) == 0) && (g.lda % 4 == 0);
+  p.b_vec = ((uintptr_t)g.B % (4 * es) == 0) && (g.ldb % 4 == 0);
+  const bool big = g.wb == 4;
+#define FDL_GX(T, EPI) do { if (big) launch_one<T, true, true, 4, EPI>(p, s); else launch_one<T, true, true, 2, EPI>(p, s); } while (0)
+  if (dt == kF32) {
+    if (kind == 1) FDL_GX(float, EPI_RELU); else if (kind == 2) FDL_GX(float, EPI_MASK); else FDL_GX(float, EPI_STORE);
+  } else {
+    if (kind == 1) FDL_GX(bf16_t, EPI_RELU); else if (kind == 2) FDL_GX(bf16_t, EPI_MASK); else FDL_GX(bf16_t, EPI_STORE);
+  }
+#undef FDL_GX
 }
 
 void launch_generic_store(int dt, const GemmDesc& g, void* C, hipStream_t s) {

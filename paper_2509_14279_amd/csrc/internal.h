@@ -79,6 +79,8 @@ struct GemmDesc {
 };
 // F1: C = Zsave [I][J] (storage type), bias [J], partial statistics part[tile][I] (float2).
 void launch_generic_f1(int dt, const GemmDesc& g, const float* bias, void* Zsave, void* part, hipStream_t s);
+// forward-product orientation with an optional bias and a ReLU or ReLU-mask epilogue (sibling operators)
+void launch_generic_xwt(int dt, int kind, const GemmDesc& g, const float* bias, const void* aux, void* C, hipStream_t s);
 // plain store: C [I][J] in the storage type
 void launch_generic_store(int dt, const GemmDesc& g, void* C, hipStream_t s);
 // plain store of the fp32 accumulators: C [I][J] float (bf16 storage; a partial sum for launch_fast_b4_reduce)
@@ -108,6 +110,14 @@ void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, bool table, const
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
                hipStream_t s);
 
+// ---- sibling operators' row-wise / element-wise kernels ------------------------------------------
+void launch_layernorm(int dt, int64_t M, int64_t N, float eps, const void* A, const float* gamma, const float* beta,
+                      void* Y, float* mean, float* rstd, hipStream_t s);
+void launch_rmsnorm(int dt, int64_t M, int64_t N, float eps, const void* A, const float* weight, void* Y, hipStream_t s);
+int colsum_groups(int64_t M);
+void launch_colsum(int dt, int64_t M, int64_t N, const void* G, void* colpart, float* out, hipStream_t s);
+void launch_silu_mul(int dt, int64_t n, const void* G, const void* U, void* H, hipStream_t s);
+
 // ---- bf16 fast path -----------------------------------------------------------------------------
 // F1 and B3 accept any M >= 128 (the last row tile may be partial); N, K as the tiles and the pipeline require.
 bool fast_f1_supported(int64_t M, int64_t K, int64_t N);
@@ -119,6 +129,9 @@ int fast_f1_stat_tile_w();
 size_t fast_f1_tail_bytes(int64_t M, int64_t K);
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
                     void* part, void* xtail, hipStream_t s);
+// sibling operators on the forward product's kernel (see gemm_bf16.hip); shapes as fast_f1_supported
+void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
+                     const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
 // dZ must have readable rows up to the next multiple of 256
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s);
 int fast_b4_split(int64_t M, int64_t K, int64_t N);

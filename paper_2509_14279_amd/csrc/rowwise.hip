@@ -42,10 +42,12 @@ __global__ __launch_bounds__(256) void stats_finalize_kernel(const f32x2* __rest
 // F2: Y = (GELU(Zsave) - mean) * rstd * gamma + beta.  A workgroup owns a strip of 256*V columns and a
 // block of rows; gamma and beta for the thread's V columns stay in registers across the rows.
 template <class T, int V>
+// (Z and Y may be the same buffer - the forward-only entry point normalises in place; each element is read by the
+// thread that writes it, before it writes it - so the two are not declared restrict.)
 __global__ __launch_bounds__(256) void f2_kernel(int64_t M, int64_t N, int rows_per_wg, int strips,
-                                                 const T* __restrict__ Z, const float* __restrict__ mean,
+                                                 const T* Z, const float* __restrict__ mean,
                                                  const float* __restrict__ rstd, const float* __restrict__ gamma,
-                                                 const float* __restrict__ beta, T* __restrict__ Y) {
+                                                 const float* __restrict__ beta, T* Y) {
   typedef typename ComputeOf<T>::type C;
   const int strip = blockIdx.x % strips;
   const int64_t rb = blockIdx.x / strips;
@@ -80,10 +82,15 @@ __global__ __launch_bounds__(256) void f2_kernel(int64_t M, int64_t N, int rows_
 // FULL: N == 512 CH, every lane holds every vector.  Otherwise the vectors past the end of the row are fetched
 // from a clamped address, masked to zero (GELU(0) = 0 adds nothing to the sum), left out of the squared
 // deviations and never stored; the code stays free of divergent branches either way.
-template <int CH, bool FULL, int NT>
-__global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float eps, const bf16_t* __restrict__ Z,
+// ACT selects what is normalised: ACT_GELU the GELU of the input (the block's second forward phase; Z and Y may then
+// be the same buffer - a lane reads its part of a row before it writes it - so they are not declared restrict),
+// ACT_NONE the input itself (stand-alone LayerNorm forward), ACT_RMS the input without mean subtraction and without
+// beta (RMSNorm forward: y = x (mean(x^2) + eps)^-1/2 w; mean and rstd are not written).
+enum { ACT_GELU = 0, ACT_NONE = 1, ACT_RMS = 2 };
+template <int CH, bool FULL, int NT, int ACT>
+__global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float eps, const bf16_t* Z,
                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                      bf16_t* __restrict__ Y, float* __restrict__ mean,
+                                                      bf16_t* Y, float* __restrict__ mean,
                                                       float* __restrict__ rstd) {
   // products are formed once and reused (fusing GELU's final multiplication into each later use would keep
   // both of its factors alive for every element of the row); the fused operations wanted are written out
@@ -94,7 +101,7 @@ __global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float
   typedef __attribute__((address_space(3))) float lds_float;
   float* htab = reinterpret_cast<float*>(gb + CH * 4 * 64);           // Phi - 1/2 for every bf16 magnitude
   const uint32_t horg = GT::origin((uint32_t)(uintptr_t)(const lds_float*)htab);
-  GT::build(htab, threadIdx.x, NT);
+  if (ACT == ACT_GELU) GT::build(htab, threadIdx.x, NT);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: row addresses stay scalar
   const int nvec = (int)(N >> 3);
@@ -103,8 +110,10 @@ __global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float
     const int c = idx >> 6, l = idx & 63;
     gb[(c * 4 + 0) * 64 + l] = *reinterpret_cast<const f32x4*>(gamma + src);
     gb[(c * 4 + 1) * 64 + l] = *reinterpret_cast<const f32x4*>(gamma + src + 4);
-    gb[(c * 4 + 2) * 64 + l] = *reinterpret_cast<const f32x4*>(beta + src);
-    gb[(c * 4 + 3) * 64 + l] = *reinterpret_cast<const f32x4*>(beta + src + 4);
+    if (ACT != ACT_RMS) {
+      gb[(c * 4 + 2) * 64 + l] = *reinterpret_cast<const f32x4*>(beta + src);
+      gb[(c * 4 + 3) * 64 + l] = *reinterpret_cast<const f32x4*>(beta + src + 4);
+    }
   }
   __syncthreads();
   const int64_t nw = (int64_t)gridDim.x * (NT / 64);
@@ -148,12 +157,22 @@ __global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float
         const uint32_t w = FULL ? raw[c][h] : (raw[c][h] & keep[c]);
         const float z0 = __builtin_bit_cast(float, w << 16);                        // bf16 -> fp32 is a 16-bit shift
         const float z1 = __builtin_bit_cast(float, w & 0xffff0000u);
-        const float h0 = *(const lds_float*)(uintptr_t)GT::address_of(w, horg);
-        const float h1 = *(const lds_float*)(uintptr_t)GT::address_of(w >> 16, horg);
-        a[c][2 * h] = z0 * (0.5f + GT::with_sign_of(h0, z0));                       // GELU(z) = z Phi(z)
-        a[c][2 * h + 1] = z1 * (0.5f + GT::with_sign_of(h1, z1));
-        sum += a[c][2 * h];
-        sum += a[c][2 * h + 1];
+        if (ACT == ACT_GELU) {
+          const float h0 = *(const lds_float*)(uintptr_t)GT::address_of(w, horg);
+          const float h1 = *(const lds_float*)(uintptr_t)GT::address_of(w >> 16, horg);
+          a[c][2 * h] = z0 * (0.5f + GT::with_sign_of(h0, z0));                     // GELU(z) = z Phi(z)
+          a[c][2 * h + 1] = z1 * (0.5f + GT::with_sign_of(h1, z1));
+        } else {
+          a[c][2 * h] = z0;
+          a[c][2 * h + 1] = z1;
+        }
+        if (ACT == ACT_RMS) {
+          sum = __builtin_fmaf(z0, z0, sum);
+          sum = __builtin_fmaf(z1, z1, sum);
+        } else {
+          sum += a[c][2 * h];
+          sum += a[c][2 * h + 1];
+        }
       }
       // One vector at a time (interleaving all of a row's evaluations would keep their temporaries alive), and as
       // soon as a vector is unpacked its registers take the same vector of the wavefront's next row: the loads
@@ -163,28 +182,41 @@ __global__ __launch_bounds__(NT) void f2_rows_kernel(int64_t M, int64_t N, float
       fetch1(c, znext);
       __builtin_amdgcn_sched_barrier(0);
     }
-    const float mu = wave_sum(sum) * inv_n;
-    float m2 = 0.0f;
+    float rs;
+    if (ACT == ACT_RMS) {
+      rs = 1.0f / __builtin_sqrtf(wave_sum(sum) * inv_n + eps);     // masked vectors hold zeros: they add nothing
+    } else {
+      const float mu = wave_sum(sum) * inv_n;
+      float m2 = 0.0f;
 #pragma unroll
-    for (int c = 0; c < CH; c++)
+      for (int c = 0; c < CH; c++)
 #pragma unroll
-      for (int v = 0; v < 8; v++) {
-        const float d = a[c][v] - mu;
-        a[c][v] = FULL ? d : (keep[c] ? d : 0.0f);
-        m2 = __builtin_fmaf(a[c][v], a[c][v], m2);
-      }
-    const float rs = 1.0f / __builtin_sqrtf(wave_sum(m2) * inv_n + eps);
-    if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+        for (int v = 0; v < 8; v++) {
+          const float d = a[c][v] - mu;
+          a[c][v] = FULL ? d : (keep[c] ? d : 0.0f);
+          m2 = __builtin_fmaf(a[c][v], a[c][v], m2);
+        }
+      rs = 1.0f / __builtin_sqrtf(wave_sum(m2) * inv_n + eps);
+      if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+    }
     bf16_t* yr = Y + row * N;
 #pragma unroll
     for (int c = 0; c < CH; c++) {
       const f32x4 g0 = gb[(c * 4 + 0) * 64 + lane], g1 = gb[(c * 4 + 1) * 64 + lane];
-      const f32x4 b0 = gb[(c * 4 + 2) * 64 + lane], b1 = gb[(c * 4 + 3) * 64 + lane];
       bf16x8 o;
+      if (ACT == ACT_RMS) {
 #pragma unroll
-      for (int v = 0; v < 4; v++) {
-        o[v] = (bf16_t)__builtin_fmaf(a[c][v] * rs, g0[v], b0[v]);
-        o[v + 4] = (bf16_t)__builtin_fmaf(a[c][v + 4] * rs, g1[v], b1[v]);
+        for (int v = 0; v < 4; v++) {
+          o[v] = (bf16_t)(a[c][v] * rs * g0[v]);
+          o[v + 4] = (bf16_t)(a[c][v + 4] * rs * g1[v]);
+        }
+      } else {
+        const f32x4 b0 = gb[(c * 4 + 2) * 64 + lane], b1 = gb[(c * 4 + 3) * 64 + lane];
+#pragma unroll
+        for (int v = 0; v < 4; v++) {
+          o[v] = (bf16_t)__builtin_fmaf(a[c][v] * rs, g0[v], b0[v]);
+          o[v + 4] = (bf16_t)__builtin_fmaf(a[c][v + 4] * rs, g1[v], b1[v]);
+        }
       }
       if (FULL) {
         bf16_t* yc = yr + c * 512;
@@ -442,6 +474,7 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
 // B2: colpart [groups][3][N] -> dbeta, dgamma, db.  64 consecutive columns per workgroup (coalesced), the groups
 // dealt over the 16 wavefronts, four independent partial sums per thread so that several loads are in flight
 // (the phase is pure latency: a few tens of MB), fp64 sums in a fixed order.
+// (nwhich = gridDim.y kinds of partial per group, colpart [groups][nwhich][N]; kind w goes to out_w)
 template <class C>
 __global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C* __restrict__ colpart,
                                                   float* __restrict__ dbeta, float* __restrict__ dgamma,
@@ -454,7 +487,7 @@ __global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C
   double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
   if (col < N) {
     const C* src = colpart + (int64_t)which * N + col;
-    const int64_t gstride = 3 * N;
+    const int64_t gstride = (int64_t)gridDim.y * N;
     int g = slice;
     for (; g + 3 * kSlices < groups; g += 4 * kSlices) {
       const C v0 = src[(int64_t)g * gstride], v1 = src[(int64_t)(g + kSlices) * gstride];
@@ -471,6 +504,99 @@ __global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C
     for (int w = 0; w < kSlices; w++) t += red[w][lane];
     float* out = which == 0 ? dbeta : (which == 1 ? dgamma : db);
     out[col] = (float)t;
+  }
+}
+
+
+// ------------------------------------------------------------------------------------------------
+// Stand-alone row normalisation for any shape and both storage types: one workgroup per row at a time, the row read
+// from memory (and then from the caches) once per pass - sum, squared deviations, output - as in the paper's
+// two-step LayerNorm and strided RMSNorm kernels.  MODE: ACT_NONE LayerNorm (writes mean, rstd), ACT_RMS RMSNorm.
+template <class T, int V, int MODE>
+__global__ __launch_bounds__(256) void norm_wg_kernel(int64_t M, int64_t N, float eps, const T* __restrict__ A,
+                                                      const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                      T* __restrict__ Y, float* __restrict__ mean, float* __restrict__ rstd) {
+  typedef typename ComputeOf<T>::type C;
+  __shared__ C red[2][4][2];
+  for (int64_t row = blockIdx.x; row < M; row += gridDim.x) {
+    const T* a = A + row * N;
+    C s1 = 0, s2 = 0;
+    for (int64_t col = (int64_t)threadIdx.x * V; col < N; col += 256 * V) {
+      C x[V];
+      VecIO<T, V>::load(a + col, x);
+#pragma unroll
+      for (int v = 0; v < V; v++) { s1 += x[v]; s2 += x[v] * x[v]; }
+    }
+    wg_sum2<C, 4>(s1, s2, red[0]);
+    C mu = 0, rs;
+    if (MODE == ACT_RMS) {
+      rs = (C)1 / sqrt(s2 / (C)N + (C)eps);
+    } else {
+      mu = s1 / (C)N;
+      C d2 = 0, dummy = 0;
+      for (int64_t col = (int64_t)threadIdx.x * V; col < N; col += 256 * V) {
+        C x[V];
+        VecIO<T, V>::load(a + col, x);
+#pragma unroll
+        for (int v = 0; v < V; v++) { const C d = x[v] - mu; d2 += d * d; }
+      }
+      wg_sum2<C, 4>(d2, dummy, red[1]);
+      rs = (C)1 / sqrt(d2 / (C)N + (C)eps);
+      if (threadIdx.x == 0) { mean[row] = (float)mu; rstd[row] = (float)rs; }
+    }
+    for (int64_t col = (int64_t)threadIdx.x * V; col < N; col += 256 * V) {
+      C x[V], y[V];
+      VecIO<T, V>::load(a + col, x);
+#pragma unroll
+      for (int v = 0; v < V; v++) {
+        if (MODE == ACT_RMS) y[v] = x[v] * rs * (C)gamma[col + v];
+        else y[v] = (x[v] - mu) * rs * (C)gamma[col + v] + (C)beta[col + v];
+      }
+      VecIO<T, V>::store(Y + row * N + col, y);
+    }
+    __syncthreads();   // the exchange slots are reused by the next row
+  }
+}
+
+// Column sums of a row-major matrix, first stage: workgroup g sums rows g, g + G, ... of a strip of 256 V columns
+// into colpart[g][N] (arithmetic type); b2_kernel finishes them.  Coalesced along the row, no atomics.
+template <class T, int V>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t M, int64_t N, int strips, int groups,
+                                                             const T* __restrict__ G,
+                                                             typename ComputeOf<T>::type* __restrict__ colpart) {
+  typedef typename ComputeOf<T>::type C;
+  const int strip = blockIdx.x % strips;
+  const int grp = blockIdx.x / strips;
+  const int64_t col = ((int64_t)strip * 256 + threadIdx.x) * V;
+  if (col >= N) return;
+  C acc[V];
+#pragma unroll
+  for (int v = 0; v < V; v++) acc[v] = 0;
+#pragma unroll 4
+  for (int64_t r = grp; r < M; r += groups) {
+    C x[V];
+    VecIO<T, V>::load(G + r * N + col, x);
+#pragma unroll
+    for (int v = 0; v < V; v++) acc[v] += x[v];
+  }
+#pragma unroll
+  for (int v = 0; v < V; v++) colpart[(int64_t)grp * N + col + v] = acc[v];
+}
+
+// H = SiLU(G) * U, element by element (the gated feed-forward block's activation); H may be G or U.
+template <class T, int V>
+__global__ __launch_bounds__(256) void silu_mul_kernel(int64_t n, const T* G, const T* U, T* H) {
+  typedef typename ComputeOf<T>::type C;
+  for (int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * V; i < n; i += (int64_t)gridDim.x * 256 * V) {
+    C g[V], u[V], h[V];
+    VecIO<T, V>::load(G + i, g);
+    VecIO<T, V>::load(U + i, u);
+#pragma unroll
+    for (int v = 0; v < V; v++) {
+      if constexpr (sizeof(C) == 8) h[v] = g[v] / (1.0 + exp(-g[v])) * u[v];
+      else h[v] = g[v] * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * g[v])) * u[v];
+    }
+    VecIO<T, V>::store(H + i, h);
   }
 }
 
@@ -574,20 +700,21 @@ void launch_f2(int dt, int64_t M, int64_t N, const void* Zsave, const float* mea
 }
 
 // one instantiation: gamma/beta (4 KB per 512 columns) plus the Phi table can exceed the default 64 KB of dynamic LDS
-template <int CH, bool FULL, int NT>
+template <int CH, bool FULL, int NT, int ACT>
 void launch_f2_rows_one(int64_t wgs, hipStream_t s, int64_t M, int64_t N, float eps, const bf16_t* Z, const float* gamma,
                         const float* beta, bf16_t* Y, float* mean, float* rstd) {
   constexpr size_t kLds = (size_t)CH * 4096 + GaussTable<false>::kBytes;
   static OnceFlags configured;
-  auto kern = f2_rows_kernel<CH, FULL, NT>;
+  auto kern = f2_rows_kernel<CH, FULL, NT, ACT>;
   if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)kLds, &configured)) return;
   hipLaunchKernelGGL(kern, dim3((unsigned)wgs), dim3(NT), kLds, s, M, N, eps, Z, gamma, beta, Y, mean, rstd);
 }
 
 bool f2_rows_supported(int dt, int64_t N) { return dt == kBF16 && N % 8 == 0 && N <= 8192; }
 
-void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const float* gamma, const float* beta, void* Y,
-                    float* mean, float* rstd, hipStream_t s) {
+template <int ACT>
+void launch_rows_act(int64_t M, int64_t N, float eps, const void* Zsave, const float* gamma, const float* beta, void* Y,
+                     float* mean, float* rstd, hipStream_t s) {
   int ch = 2;
   while (ch * 512 < N) ch *= 2;
   const bool full = N == (int64_t)ch * 512;
@@ -600,7 +727,7 @@ void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const fl
   const int64_t cap = (int64_t)di.cus * (16 / ch);
   if (wgs > cap) wgs = cap;
 #define FDL_F2R(CHH, FULL, NTT)                                                                                    \
-  launch_f2_rows_one<CHH, FULL, NTT>(wgs, s, M, N,                                                                      \
+  launch_f2_rows_one<CHH, FULL, NTT, ACT>(wgs, s, M, N,                                                                 \
                      eps, (const bf16_t*)Zsave, gamma, beta, (bf16_t*)Y, mean, rstd)
   if (full) {
     if (ch == 2) FDL_F2R(2, true, 512); else if (ch == 4) FDL_F2R(4, true, 512);
@@ -610,6 +737,78 @@ void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const fl
     else if (ch == 8) FDL_F2R(8, false, 512); else FDL_F2R(16, false, 256);
   }
 #undef FDL_F2R
+}
+
+void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const float* gamma, const float* beta, void* Y,
+                    float* mean, float* rstd, hipStream_t s) {
+  launch_rows_act<ACT_GELU>(M, N, eps, Zsave, gamma, beta, Y, mean, rstd, s);
+}
+
+
+bool rows_act_supported(int dt, int64_t N) { return f2_rows_supported(dt, N); }
+
+template <class T, int MODE>
+static void norm_wg_impl(int64_t M, int64_t N, float eps, const void* A, const float* gamma, const float* beta, void* Y,
+                         float* mean, float* rstd, hipStream_t s) {
+  constexpr int VMAX = 16 / (int)sizeof(T);
+  const bool vec = N % VMAX == 0 && ((uintptr_t)A | (uintptr_t)Y) % 16 == 0;
+  const unsigned blocks = (unsigned)(M < 8192 ? M : 8192);
+  if (vec) hipLaunchKernelGGL((norm_wg_kernel<T, VMAX, MODE>), dim3(blocks), dim3(256), 0, s, M, N, eps, (const T*)A, gamma, beta, (T*)Y, mean, rstd);
+  else hipLaunchKernelGGL((norm_wg_kernel<T, 1, MODE>), dim3(blocks), dim3(256), 0, s, M, N, eps, (const T*)A, gamma, beta, (T*)Y, mean, rstd);
+}
+
+// Y = LayerNorm(A) gamma + beta over the last dimension; mean, rstd [M] out
+void launch_layernorm(int dt, int64_t M, int64_t N, float eps, const void* A, const float* gamma, const float* beta,
+                      void* Y, float* mean, float* rstd, hipStream_t s) {
+  if (rows_act_supported(dt, N)) launch_rows_act<ACT_NONE>(M, N, eps, A, gamma, beta, Y, mean, rstd, s);
+  else if (dt == kF32) norm_wg_impl<float, ACT_NONE>(M, N, eps, A, gamma, beta, Y, mean, rstd, s);
+  else norm_wg_impl<bf16_t, ACT_NONE>(M, N, eps, A, gamma, beta, Y, mean, rstd, s);
+}
+
+// Y = A (mean(A^2) + eps)^-1/2 weight over the last dimension
+void launch_rmsnorm(int dt, int64_t M, int64_t N, float eps, const void* A, const float* weight, void* Y, hipStream_t s) {
+  if (rows_act_supported(dt, N)) launch_rows_act<ACT_RMS>(M, N, eps, A, weight, weight, Y, nullptr, nullptr, s);
+  else if (dt == kF32) norm_wg_impl<float, ACT_RMS>(M, N, eps, A, weight, weight, Y, nullptr, nullptr, s);
+  else norm_wg_impl<bf16_t, ACT_RMS>(M, N, eps, A, weight, weight, Y, nullptr, nullptr, s);
+}
+
+// groups of the first stage of a column sum over M rows
+int colsum_groups(int64_t M) { return (int)(M < 256 ? (M > 0 ? M : 1) : 256); }
+
+// out[j] = sum_i G[i][j]; colpart: colsum_groups(M) * N values of the arithmetic type
+void launch_colsum(int dt, int64_t M, int64_t N, const void* G, void* colpart, float* out, hipStream_t s) {
+  const int groups = colsum_groups(M);
+  const int vmax = dt == kF32 ? 4 : 8;
+  const bool vec = N % vmax == 0 && (uintptr_t)G % 16 == 0;
+  const int V = vec ? vmax : 1;
+  const int strips = (int)((N + 256 * (int64_t)V - 1) / (256 * (int64_t)V));
+  const dim3 grid((unsigned)(strips * groups));
+  if (dt == kF32) {
+    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<float, 4>), grid, dim3(256), 0, s, M, N, strips, groups, (const float*)G, (double*)colpart);
+    else hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), grid, dim3(256), 0, s, M, N, strips, groups, (const float*)G, (double*)colpart);
+    hipLaunchKernelGGL((b2_kernel<double>), dim3((unsigned)((N + 63) / 64), 1), dim3(1024), 0, s, N, groups, (const double*)colpart, out, out, out);
+  } else {
+    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 8>), grid, dim3(256), 0, s, M, N, strips, groups, (const bf16_t*)G, (float*)colpart);
+    else hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 1>), grid, dim3(256), 0, s, M, N, strips, groups, (const bf16_t*)G, (float*)colpart);
+    hipLaunchKernelGGL((b2_kernel<float>), dim3((unsigned)((N + 63) / 64), 1), dim3(1024), 0, s, N, groups, (const float*)colpart, out, out, out);
+  }
+}
+
+// H = SiLU(G) * U over n elements (H may alias G or U)
+void launch_silu_mul(int dt, int64_t n, const void* G, const void* U, void* H, hipStream_t s) {
+  const int vmax = dt == kF32 ? 4 : 8;
+  const bool vec = n % vmax == 0 && ((uintptr_t)G | (uintptr_t)U | (uintptr_t)H) % 16 == 0;
+  const int64_t per = 256 * (int64_t)(vec ? vmax : 1);
+  int64_t blocks = (n + per - 1) / per;
+  if (blocks > 16384) blocks = 16384;
+  if (blocks < 1) blocks = 1;
+  if (dt == kF32) {
+    if (vec) hipLaunchKernelGGL((silu_mul_kernel<float, 4>), dim3((unsigned)blocks), dim3(256), 0, s, n, (const float*)G, (const float*)U, (float*)H);
+    else hipLaunchKernelGGL((silu_mul_kernel<float, 1>), dim3((unsigned)blocks), dim3(256), 0, s, n, (const float*)G, (const float*)U, (float*)H);
+  } else {
+    if (vec) hipLaunchKernelGGL((silu_mul_kernel<bf16_t, 8>), dim3((unsigned)blocks), dim3(256), 0, s, n, (const bf16_t*)G, (const bf16_t*)U, (bf16_t*)H);
+    else hipLaunchKernelGGL((silu_mul_kernel<bf16_t, 1>), dim3((unsigned)blocks), dim3(256), 0, s, n, (const bf16_t*)G, (const bf16_t*)U, (bf16_t*)H);
+  }
 }
 
 void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave, const float* gamma, const float* mean,

@@ -99,3 +99,28 @@ def generate(cfg: Config, with_dY: bool = True) -> Dict[str, torch.Tensor]:
 
 def storage_torch_dtype(dtype: str) -> torch.dtype:
     return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+# ---------------------------------------------------------------- sibling operators (draws and rounding only)
+def generate_norm(dtype: str, M: int, N: int, seed: int, mean: float = 0.5, std: float = 2.0) -> Dict[str, torch.Tensor]:
+    """Inputs of the stand-alone row normalisations: A [M,N] ~ N(mean, std^2) rounded to the storage type; gamma
+    (also the RMSNorm weight) = 1 + N(0, 0.1), beta ~ N(0, 0.1) in full fp32 (they are fp32 by contract).
+    Draw order: A, gamma, beta."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    A = torch.randn(M, N, generator=g, dtype=torch.float32).mul_(std).add_(mean)
+    gamma = torch.randn(N, generator=g, dtype=torch.float32).mul_(math.sqrt(0.1)).add_(1.0)
+    beta = torch.randn(N, generator=g, dtype=torch.float32).mul_(math.sqrt(0.1))
+    return {"A": _round_to_storage(A, dtype), "gamma": gamma, "beta": beta}
+
+
+def generate_ffn(dtype: str, M: int, D: int, H: int, seed: int) -> Dict[str, torch.Tensor]:
+    """Inputs of the gated feed-forward block: X [M,D] ~ N(0,1); Wg, Wu [H,D] ~ N(0, 1/D); Wd [D,H] ~ N(0, 1/H); all
+    rounded to the storage type.  Draw order: X, Wg, Wu, Wd."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(seed)
+    X = torch.randn(M, D, generator=g, dtype=torch.float32)
+    Wg = torch.randn(H, D, generator=g, dtype=torch.float32).mul_(1.0 / math.sqrt(D))
+    Wu = torch.randn(H, D, generator=g, dtype=torch.float32).mul_(1.0 / math.sqrt(D))
+    Wd = torch.randn(D, H, generator=g, dtype=torch.float32).mul_(1.0 / math.sqrt(H))
+    return {k: _round_to_storage(v, dtype) for k, v in {"X": X, "Wg": Wg, "Wu": Wu, "Wd": Wd}.items()}

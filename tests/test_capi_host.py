@@ -129,3 +129,49 @@ def test_one_hip_runtime_in_the_process():
     assert len(loaded) == 1, loaded
     import torch
     assert os.path.dirname(torch.__file__) in next(iter(loaded))
+
+
+def test_sibling_entry_points_reject_bad_arguments_before_any_launch():
+    big = 1 << 30
+    # forward for inference
+    assert api.fdl_forward_inference_workspace_bytes("bf16", 65536, 2048, 8192) < 1 << 22      # row statistics only
+    assert api.fdl_forward_inference_workspace_bytes(9, 8, 8, 8) == 0
+    assert api.fdl_forward_inference_raw("f32", 4, 4, 4, 0, P, P, P, P, 1e-5, P, P, big, None) == api.FDL_ERR_NULL
+    assert api.fdl_forward_inference_raw("f32", 4, 4, 4, P, P, P, P, P, 1e-5, 0, P, big, None) == api.FDL_ERR_NULL
+    assert api.fdl_forward_inference_raw(3, 4, 4, 4, P, P, P, P, P, 1e-5, P, P, big, None) == api.FDL_ERR_DTYPE
+    assert api.fdl_forward_inference_raw("f32", 4, 0, 4, P, P, P, P, P, 1e-5, P, P, big, None) == api.FDL_ERR_SHAPE
+    assert api.fdl_forward_inference_raw("f32", 4, 4, 4, P, P, P, P, P, -1.0, P, P, big, None) == api.FDL_ERR_EPS
+    assert api.fdl_forward_inference_raw("f32", 4, 4, 4, P, P, P, P, P, 1e-5, P, P, 8, None) == api.FDL_ERR_WORKSPACE
+    assert api.fdl_forward_inference_raw("f32", 4, 4, 4, P, P, P, P, P, 1e-5, P, P + 16, big, None) == api.FDL_ERR_ALIGN
+    assert api.fdl_forward_inference_raw("f32", 4, 4, 4, P + 4, P, P, P, P, 1e-5, P, P, big, None) == api.FDL_ERR_ALIGN
+    assert api.fdl_forward_inference_raw("f32", 0, 4, 4, P, P, P, P, P, 1e-5, P, P, big, None) == api.FDL_OK
+    # Linear + ReLU
+    assert api.fdl_linear_relu_workspace_bytes("bf16", 4096, 512, 1024) >= 4096 * 1024 * 2
+    assert api.fdl_linear_relu_workspace_bytes("f32", 8, 0, 8) == 0
+    assert api.fdl_linear_relu_forward_raw("f32", 4, 4, 4, P, 0, P, P, P, big, None) == api.FDL_ERR_NULL
+    assert api.fdl_linear_relu_forward_raw(7, 4, 4, 4, P, P, P, P, P, big, None) == api.FDL_ERR_DTYPE
+    assert api.fdl_linear_relu_forward_raw("f32", -1, 4, 4, P, P, P, P, P, big, None) == api.FDL_ERR_SHAPE
+    assert api.fdl_linear_relu_forward_raw("f32", 4, 4, 4, P, P, P, P, 0, big, None) == api.FDL_ERR_WORKSPACE
+    assert api.fdl_linear_relu_forward_raw("f32", 4, 4, 4, P, P, P, P + 2, P, big, None) == api.FDL_ERR_ALIGN
+    assert api.fdl_linear_relu_backward_raw("f32", 4, 4, 4, P, P, P, P, P, P, 0, P, big, None) == api.FDL_ERR_NULL
+    assert api.fdl_linear_relu_backward_raw("f32", 4, 4, 4, P, P, P, P, P, P, P, P, 8, None) == api.FDL_ERR_WORKSPACE
+    assert api.fdl_linear_relu_backward_raw("f32", 4, 4, 0, P, P, P, P, P, P, P, P, big, None) == api.FDL_ERR_SHAPE
+    assert api.fdl_linear_relu_backward_raw("f32", 4, 4, 4, P, P, P, P, P + 8, P, P, P, big, None) == api.FDL_ERR_ALIGN
+    # norms
+    assert api.fdl_layernorm_forward_raw("f32", 4, 4, P, P, P, 1e-5, P, P, 0, None) == api.FDL_ERR_NULL
+    assert api.fdl_layernorm_forward_raw("f32", 4, 0, P, P, P, 1e-5, P, P, P, None) == api.FDL_ERR_SHAPE
+    assert api.fdl_layernorm_forward_raw("f32", 4, 4, P, P, P, float("nan"), P, P, P, None) == api.FDL_ERR_EPS
+    assert api.fdl_layernorm_forward_raw(2, 4, 4, P, P, P, 1e-5, P, P, P, None) == api.FDL_ERR_DTYPE
+    assert api.fdl_layernorm_forward_raw("f32", 4, 4, P, P + 4, P, 1e-5, P, P, P, None) == api.FDL_ERR_ALIGN
+    assert api.fdl_rmsnorm_forward_raw("f32", 4, 4, P, 0, 1e-5, P, None) == api.FDL_ERR_NULL
+    assert api.fdl_rmsnorm_forward_raw("f32", 1 << 25, 4, P, P, 1e-5, P, None) == api.FDL_ERR_SHAPE
+    assert api.fdl_rmsnorm_forward_raw("f32", 4, 4, P, P, -1.0, P, None) == api.FDL_ERR_EPS
+    assert api.fdl_rmsnorm_forward_raw("f32", 0, 4, P, P, 1e-5, P, None) == api.FDL_OK
+    # Llama feed-forward
+    assert api.fdl_llama_ffn_workspace_bytes("bf16", 1024, 512, 2048) >= 2 * 1024 * 2048 * 2
+    assert api.fdl_llama_ffn_workspace_bytes("bf16", 1024, 0, 2048) == 0
+    assert api.fdl_llama_ffn_forward_raw("f32", 4, 4, 4, P, P, 0, P, P, P, big, None) == api.FDL_ERR_NULL
+    assert api.fdl_llama_ffn_forward_raw("f32", 4, 4, 0, P, P, P, P, P, P, big, None) == api.FDL_ERR_SHAPE
+    assert api.fdl_llama_ffn_forward_raw("f32", 4, 4, 4, P, P, P, P, P, P, 8, None) == api.FDL_ERR_WORKSPACE
+    assert api.fdl_llama_ffn_forward_raw("f32", 4, 4, 4, P, P, P, P + 4, P, P, big, None) == api.FDL_ERR_ALIGN
+    assert api.fdl_llama_ffn_forward_raw(-1, 4, 4, 4, P, P, P, P, P, P, big, None) == api.FDL_ERR_DTYPE

@@ -1,0 +1,233 @@
+"""GPU parity of the forward-only variant and the sibling operators (through the C ABI) against their fp64 oracles
+on seeded inputs.  Bars as for the block itself: fp32 storage -> every element within atol 1e-5 + rtol 1e-4 |ref|;
+bf16 storage -> max|err| / max|ref| <= 2e-2 per output tensor.  Every output buffer is surrounded by guard bytes."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fdl_oracle as O
+from oracle import siblings_oracle as S
+from paper_2509_14279_amd import api, inputs as I
+import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def f64(t):
+    return {k: v.numpy().astype(np.float64) for k, v in t.items()}
+
+
+def dev(t, dtype, matrices):
+    dt = I.storage_torch_dtype(dtype)
+    return {k: (v.to("cuda", dt) if k in matrices else v.to("cuda")) for k, v in t.items()}
+
+
+def guarded_ws(nbytes):
+    ws = H.Guarded((max(nbytes, 256),), torch.uint8)
+    assert ws.view.data_ptr() % 256 == 0
+    return ws
+
+
+def finish(outs, ws=None):
+    torch.cuda.synchronize()
+    for k, g in outs.items():
+        assert g.intact(), f"kernel wrote outside the {k} buffer"
+    if ws is not None:
+        assert ws.intact(), "kernel wrote outside the workspace"
+
+
+# (dtype, M, K, N): fast path exact / ragged M / rows beyond the row-resident normalisation; generic kernels; fp32
+BLOCK_SHAPES = [("bf16", 512, 256, 1024), ("bf16", 300, 256, 512), ("bf16", 256, 128, 8448), ("bf16", 130, 70, 200),
+                ("bf16", 31, 515, 1030), ("f32", 130, 70, 200), ("f32", 257, 19, 300), ("f32", 100, 64, 4100),
+                ("bf16", 2304, 768, 2560), ("f32", 1, 1, 1), ("bf16", 5, 1, 3)]
+
+
+# ------------------------------------------------------------------ forward for inference
+@pytest.mark.parametrize("dtype,M,K,N", BLOCK_SHAPES)
+def test_forward_inference_matches_oracle_and_training_forward(dtype, M, K, N):
+    cfg = I.custom(dtype, M, K, N, seed=6000 + M + K + N)
+    t = I.generate(cfg, with_dY=False)
+    say(f"[inference] {cfg.name}")
+    d = dev(t, dtype, ("X", "W"))
+    dt = I.storage_torch_dtype(dtype)
+    Y = H.Guarded((M, N), dt)
+    ws = guarded_ws(api.fdl_forward_inference_workspace_bytes(dtype, M, K, N))
+    api.fdl_forward_inference(dtype, d["X"], d["W"], d["b"], d["gamma"], d["beta"], cfg.eps, Y.view, ws.view)
+    finish({"Y": Y}, ws)
+    n = f64(t)
+    ref = O.forward(n["X"], n["W"], n["b"], n["gamma"], n["beta"], cfg.eps)
+    H.set_ratio_label(cfg.name + "/inference")
+    H.check(dtype, "Y", H.to_f64(Y.view), ref["Y"], f32_atol=1e-3 if N == 1 else 1e-5)
+    # the same kernels as the training forward: bit-identical Y, and a much smaller workspace
+    full = H.run_fdl(cfg, t, backward=False)
+    assert torch.equal(full["Y"].view(torch.uint8), Y.view.view(torch.uint8))
+    assert api.fdl_forward_inference_workspace_bytes(dtype, M, K, N) < api.fdl_workspace_bytes(dtype, M, K, N)
+
+
+# ------------------------------------------------------------------ Linear + ReLU
+def relu_mask_slack(n, ref_b, acc_unit):
+    """Elements whose exact pre-activation is within the contraction's rounding of zero may take either side of the
+    mask: the bound on what such elements can add to each output (oracle side)."""
+    Z = ref_b["Z"]
+    S_Z = np.abs(n["X"]) @ np.abs(n["W"]).T + np.abs(n["b"])[None, :]
+    amb = np.abs(Z) <= 8 * acc_unit * S_Z
+    Gamb = np.abs(n["dY"]) * amb
+    return {"dX": Gamb @ np.abs(n["W"]), "dW": Gamb.T @ np.abs(n["X"]), "db": Gamb.sum(axis=0)}, int(amb.sum())
+
+
+@pytest.mark.parametrize("dtype,M,K,N", BLOCK_SHAPES + [("bf16", 1000, 256, 768), ("bf16", 4096, 512, 1024)])
+def test_linear_relu_forward_and_backward(dtype, M, K, N):
+    cfg = I.custom(dtype, M, K, N, seed=6500 + M + K + N)
+    t = I.generate(cfg)
+    say(f"[linear-relu] {cfg.name}")
+    d = dev(t, dtype, ("X", "W", "dY"))
+    dt = I.storage_torch_dtype(dtype)
+    out = {"Y": H.Guarded((M, N), dt), "dX": H.Guarded((M, K), dt), "dW": H.Guarded((N, K), dt),
+           "db": H.Guarded((N,), torch.float32)}
+    ws = guarded_ws(api.fdl_linear_relu_workspace_bytes(dtype, M, K, N))
+    api.fdl_linear_relu_forward(dtype, d["X"], d["W"], d["b"], out["Y"].view, ws.view)
+    api.fdl_linear_relu_backward(dtype, d["dY"], d["X"], d["W"], d["b"], out["dX"].view, out["dW"].view, out["db"].view, ws.view)
+    finish(out, ws)
+    n = f64(t)
+    ref_f = S.linear_relu_forward(n["X"], n["W"], n["b"])
+    ref_b = S.linear_relu_backward(n["dY"], n["X"], n["W"], n["b"])
+    H.set_ratio_label(cfg.name + "/linear_relu")
+    H.check(dtype, "Y", H.to_f64(out["Y"].view), ref_f["Y"])
+    assert float(out["Y"].view.float().min()) >= 0.0
+    slack, namb = relu_mask_slack(n, ref_b, 2.0 ** -24 if dtype == "bf16" else 2.0 ** -53)
+    for k in ("dX", "dW", "db"):
+        got = H.to_f64(out[k].view)
+        if namb == 0:
+            H.check(dtype, k, got, ref_b[k])
+        elif dtype == "f32":
+            assert np.all(np.abs(got - ref_b[k]) <= 1e-5 + 1e-4 * np.abs(ref_b[k]) + slack[k]), k
+        else:
+            assert np.all(np.abs(got - ref_b[k]) <= 2e-2 * np.abs(ref_b[k]).max() + slack[k]), k
+
+
+def test_linear_relu_backward_all_negative_and_all_positive_masks():
+    """A large negative bias closes every unit (all gradients exactly zero); a large positive one opens every unit
+    (the plain linear-layer gradients)."""
+    cfg = I.custom("bf16", 512, 256, 512, seed=6600)
+    t = I.generate(cfg)
+    dt = torch.bfloat16
+    for shift in (-200.0, 200.0):
+        t["b"] = torch.full((cfg.N,), shift)
+        d = dev(t, "bf16", ("X", "W", "dY"))
+        dX = torch.full((cfg.M, cfg.K), 3.0, device="cuda", dtype=dt); dW = torch.full((cfg.N, cfg.K), 3.0, device="cuda", dtype=dt)
+        db = torch.full((cfg.N,), 3.0, device="cuda")
+        ws = torch.empty(api.fdl_linear_relu_workspace_bytes("bf16", cfg.M, cfg.K, cfg.N), dtype=torch.uint8, device="cuda")
+        api.fdl_linear_relu_backward("bf16", d["dY"], d["X"], d["W"], d["b"], dX, dW, db, ws)
+        torch.cuda.synchronize()
+        n = f64(t)
+        if shift < 0:
+            assert float(dX.float().abs().max()) == 0.0 and float(dW.float().abs().max()) == 0.0 and float(db.abs().max()) == 0.0
+        else:
+            H.check_bf16("dX", H.to_f64(dX), n["dY"] @ n["W"])
+            H.check_bf16("dW", H.to_f64(dW), n["dY"].T @ n["X"])
+            H.check_bf16("db", H.to_f64(db), n["dY"].sum(axis=0))
+
+
+# ------------------------------------------------------------------ LayerNorm / RMSNorm forward
+# bf16: row-resident kernel (exact fits 1024 / 8192, masked tails 4352 / 7936), generic kernel (unaligned 100 / 2051,
+# long 8200 / 16384); fp32: generic kernel with and without vector loads; single rows, single columns
+NORM_SHAPES = [("bf16", 300, 1024), ("bf16", 64, 8192), ("bf16", 129, 4352), ("bf16", 33, 7936), ("bf16", 50, 100),
+               ("bf16", 16, 2051), ("bf16", 24, 8200), ("bf16", 10, 16384), ("f32", 130, 200), ("f32", 31, 1537),
+               ("f32", 12, 4100), ("f32", 1, 1), ("bf16", 7, 1), ("bf16", 1, 8), ("f32", 5, 2), ("bf16", 9000, 512)]
+
+
+@pytest.mark.parametrize("dtype,M,N", NORM_SHAPES)
+def test_layernorm_forward(dtype, M, N):
+    t = I.generate_norm(dtype, M, N, seed=7000 + M + N)
+    say(f"[layernorm] {dtype} {M}x{N}")
+    d = dev(t, dtype, ("A",))
+    dt = I.storage_torch_dtype(dtype)
+    out = {"Y": H.Guarded((M, N), dt), "mean": H.Guarded((M,), torch.float32), "rstd": H.Guarded((M,), torch.float32)}
+    api.fdl_layernorm_forward(dtype, d["A"], d["gamma"], d["beta"], 1e-5, out["Y"].view, out["mean"].view, out["rstd"].view)
+    finish(out)
+    n = f64(t)
+    ref = S.layernorm_forward(n["A"], n["gamma"], n["beta"], 1e-5)
+    H.set_ratio_label(f"layernorm_{dtype}_{M}x{N}")
+    H.check(dtype, "Y", H.to_f64(out["Y"].view), ref["Y"], f32_atol=1e-3 if N == 1 else 1e-5)
+    H.check(dtype, "mean", H.to_f64(out["mean"].view), ref["mean"])
+    np.testing.assert_allclose(H.to_f64(out["rstd"].view), ref["rstd"], rtol=1e-4 if dtype == "f32" else 2e-2)
+
+
+@pytest.mark.parametrize("dtype,M,N", NORM_SHAPES)
+def test_rmsnorm_forward(dtype, M, N):
+    t = I.generate_norm(dtype, M, N, seed=7500 + M + N)
+    say(f"[rmsnorm] {dtype} {M}x{N}")
+    d = dev(t, dtype, ("A",))
+    out = {"Y": H.Guarded((M, N), I.storage_torch_dtype(dtype))}
+    api.fdl_rmsnorm_forward(dtype, d["A"], d["gamma"], 1e-5, out["Y"].view)
+    finish(out)
+    n = f64(t)
+    ref = S.rmsnorm_forward(n["A"], n["gamma"], 1e-5)
+    H.set_ratio_label(f"rmsnorm_{dtype}_{M}x{N}")
+    H.check(dtype, "Y", H.to_f64(out["Y"].view), ref["Y"])
+
+
+def test_norms_constant_and_zero_rows():
+    """A constant row has zero variance (LayerNorm gives beta; eps keeps rstd finite); an all-zero row has zero mean
+    square (RMSNorm gives zero)."""
+    for dtype in ("f32", "bf16"):
+        dt = I.storage_torch_dtype(dtype)
+        A = torch.zeros(6, 264); A[1] = 3.25; A[3] = -0.5
+        t = I.generate_norm(dtype, 6, 264, seed=1)
+        Y = torch.empty(6, 264, device="cuda", dtype=dt); mean = torch.empty(6, device="cuda"); rstd = torch.empty(6, device="cuda")
+        api.fdl_layernorm_forward(dtype, A.to("cuda", dt), t["gamma"].cuda(), t["beta"].cuda(), 1e-5, Y, mean, rstd)
+        torch.cuda.synchronize()
+        np.testing.assert_allclose(H.to_f64(Y), np.broadcast_to(t["beta"].numpy(), (6, 264)), atol=1e-2 if dtype == "bf16" else 1e-3)
+        api.fdl_rmsnorm_forward(dtype, A.to("cuda", dt), t["gamma"].cuda(), 1e-5, Y)
+        torch.cuda.synchronize()
+        ref = S.rmsnorm_forward(A.numpy(), t["gamma"].numpy(), 1e-5)["Y"]
+        H.check(dtype, "Y", H.to_f64(Y), ref)
+        assert float(Y[0].float().abs().max()) == 0.0
+
+
+# ------------------------------------------------------------------ Llama feed-forward block
+# (dtype, M, D, H): fast path exact and with a ragged M; generic kernels (unaligned D or H); fp32
+FFN_SHAPES = [("bf16", 512, 512, 1024), ("bf16", 300, 256, 768), ("bf16", 1024, 1024, 2816), ("bf16", 130, 100, 200),
+              ("bf16", 64, 256, 264), ("f32", 130, 70, 200), ("f32", 33, 64, 128), ("f32", 1, 1, 1), ("bf16", 3, 5, 7)]
+
+
+@pytest.mark.parametrize("dtype,M,D,Hd", FFN_SHAPES)
+def test_llama_ffn_forward(dtype, M, D, Hd):
+    t = I.generate_ffn(dtype, M, D, Hd, seed=8000 + M + D + Hd)
+    say(f"[llama-ffn] {dtype} {M}x{D}x{Hd}")
+    d = dev(t, dtype, ("X", "Wg", "Wu", "Wd"))
+    out = {"Y": H.Guarded((M, D), I.storage_torch_dtype(dtype))}
+    ws = guarded_ws(api.fdl_llama_ffn_workspace_bytes(dtype, M, D, Hd))
+    api.fdl_llama_ffn_forward(dtype, d["X"], d["Wg"], d["Wu"], d["Wd"], out["Y"].view, ws.view)
+    finish(out, ws)
+    n = f64(t)
+    ref = S.llama_ffn_forward(n["X"], n["Wg"], n["Wu"], n["Wd"])
+    H.set_ratio_label(f"llama_ffn_{dtype}_{M}x{D}x{Hd}")
+    H.check(dtype, "Y", H.to_f64(out["Y"].view), ref["Y"])
+    # anti-shortcut: the output varies along both axes
+    if M > 2 and D > 2:
+        y = H.to_f64(out["Y"].view)
+        assert y.std(axis=0).min() > 1e-4 and y.std(axis=1).min() > 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_siblings_empty_batch(dtype):
+    dt = I.storage_torch_dtype(dtype)
+    z = torch.zeros(64, device="cuda", dtype=dt); f = torch.zeros(64, device="cuda")
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    assert api.fdl_forward_inference_raw(dtype, 0, 8, 16, z, z, f, f, f, 1e-5, z, ws, ws.numel(), None) == api.FDL_OK
+    assert api.fdl_linear_relu_forward_raw(dtype, 0, 8, 16, z, z, f, z, ws, ws.numel(), None) == api.FDL_OK
+    dW = torch.full((16, 8), 3.0, device="cuda").to(dt); db = torch.full((16,), 3.0, device="cuda")
+    assert api.fdl_linear_relu_backward_raw(dtype, 0, 8, 16, z, z, z, f, z, dW, db, ws, ws.numel(), None) == api.FDL_OK
+    assert api.fdl_layernorm_forward_raw(dtype, 0, 16, z, f, f, 1e-5, z, f, f, None) == api.FDL_OK
+    assert api.fdl_rmsnorm_forward_raw(dtype, 0, 16, z, f, 1e-5, z, None) == api.FDL_OK
+    assert api.fdl_llama_ffn_forward_raw(dtype, 0, 8, 16, z, z, z, z, z, ws, ws.numel(), None) == api.FDL_OK
+    torch.cuda.synchronize()
+    assert float(dW.float().abs().max()) == 0.0 and float(db.abs().max()) == 0.0
