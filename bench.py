@@ -16,6 +16,7 @@ published peaks (`measured_peak`, `frac_of_measured`, `frac_measured`).
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 0..4]
     python bench.py --ceilings        # the ceilings alone, as a text table (with LDS access-pattern probes)
     python bench.py --sweep           # throughput over tuned and untuned shapes
+    python bench.py --siblings        # the forward-only entry point and the sibling operators at the headline's scale
 """
 from __future__ import annotations
 
@@ -293,7 +294,7 @@ SWEEP_SHAPES = [
     ("tuned", "bf16", 65536, 2048, 8192), ("tuned", "bf16", 8192, 1024, 4096), ("tuned", "bf16", 16384, 4096, 4096),
     ("untuned", "bf16", 32768, 1024, 1024), ("untuned", "bf16", 16384, 1536, 3072), ("untuned", "bf16", 4096, 4096, 16384),
     ("untuned", "bf16", 2048, 8192, 512), ("untuned", "bf16", 131072, 512, 2048), ("untuned", "bf16", 8192, 2048, 32768),
-    ("untuned", "bf16", 10000, 1024, 3072), ("untuned", "bf16", 50001, 2048, 4096), ("untuned", "bf16", 10000, 1000, 3000), ("untuned", "bf16", 16384, 1024, 64), ("untuned", "bf16", 4096, 1024, 8200),
+    ("untuned", "bf16", 10000, 1024, 3072), ("untuned", "bf16", 50001, 2048, 4096), ("untuned", "bf16", 10000, 1000, 3000), ("untuned", "bf16", 16384, 1024, 64), ("untuned", "bf16", 4096, 1024, 8192), ("untuned", "bf16", 4096, 1024, 8200),
     ("tuned", "f32", 3001, 771, 1537), ("untuned", "f32", 4096, 1024, 2048),
 ]
 
@@ -345,6 +346,108 @@ def run_sweep(steps: int, warmup: int):
         del X, W, dY, Y, Z, dX, dW, ws
 
 
+def run_siblings(steps: int, warmup: int, cpu: bool):
+    """The forward-only entry point and the sibling operators at the headline's scale: per operator the time per call
+    (HIP events around `steps` calls), its algorithmic work against the published peak, the oracle timed on a bounded
+    sample on the host cores, and the same operator in torch eager on this GPU as context.  One JSON line each."""
+    import numpy as np
+    import torch
+    import torch.nn.functional as F
+    from paper_2509_14279_amd import api, inputs as I
+    from oracle import fdl_oracle as O, siblings_oracle as S
+    dev = torch.device("cuda:0")
+    bf = torch.bfloat16
+    g = torch.Generator(device=dev); g.manual_seed(123)
+    rnd = lambda *sh: torch.randn(*sh, device=dev, generator=g)
+
+    def timeit(fn):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize(); e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    def cpu_time(fn):
+        t0 = time.perf_counter(); fn(); return time.perf_counter() - t0
+
+    def report(name, shape, ms, flop=None, nbytes=None, eager_ms=None, cpu_s=None, cpu_note=None):
+        out = {"op": name, "shape": shape, "dtype": "bf16", "ms": round(ms, 4)}
+        if flop:
+            out.update({"TFLOP/s": round(flop / ms / 1e9, 1), "frac_mfma_peak": round(flop / ms / 1e9 / PEAK_TFLOPS["bf16"], 4)})
+        if nbytes:
+            out.update({"GB/s": round(nbytes / ms / 1e6, 1), "frac_hbm_peak": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4)})
+        if eager_ms is not None:
+            out["torch_eager_ms"] = round(eager_ms, 4)
+        if cpu_s is not None:
+            out["cpu_oracle"] = {"seconds": round(cpu_s, 2), "sample": cpu_note}
+        print(json.dumps(out), flush=True)
+
+    M, K, N = 65536, 2048, 8192
+    X = rnd(M, K).to(bf); W = (rnd(N, K) / K ** 0.5).to(bf); dY = rnd(M, N).to(bf)
+    b = rnd(N) * 0.14; gm = 1 + 0.3 * rnd(N); bt = 0.3 * rnd(N)
+    Y = torch.empty(M, N, device=dev, dtype=bf)
+    st = torch.cuda.current_stream()
+    rows = 2048          # rows of the workload the CPU oracle is timed on
+    Xc, Wc = X[:rows].float().cpu().numpy(), W.float().cpu().numpy()
+    bc, gc, btc, dYc = b.cpu().numpy(), gm.cpu().numpy(), bt.cpu().numpy(), dY[:rows].float().cpu().numpy()
+    note = f"first {rows} of {M} rows, fp64 numpy"
+
+    # forward for inference
+    ws = torch.empty(api.fdl_forward_inference_workspace_bytes("bf16", M, K, N), dtype=torch.uint8, device=dev)
+    ms = timeit(lambda: api.fdl_forward_inference("bf16", X, W, b, gm, bt, 1e-5, Y, ws, st))
+    bb, gg, btt = b.to(bf), gm.to(bf), bt.to(bf)
+    eager = timeit(lambda: F.layer_norm(F.gelu(F.linear(X, W, bb)), (N,), gg, btt, 1e-5))
+    report("fdl_forward_inference", [M, K, N], ms, flop=2.0 * M * N * K, eager_ms=eager,
+           cpu_s=cpu_time(lambda: O.forward(Xc, Wc, bc, gc, btc, 1e-5)) if cpu else None, cpu_note=note)
+
+    # Linear + ReLU
+    ws = torch.empty(api.fdl_linear_relu_workspace_bytes("bf16", M, K, N), dtype=torch.uint8, device=dev)
+    ms = timeit(lambda: api.fdl_linear_relu_forward("bf16", X, W, b, Y, ws, st))
+    eager = timeit(lambda: F.relu(F.linear(X, W, bb)))
+    report("fdl_linear_relu_forward", [M, K, N], ms, flop=2.0 * M * N * K, eager_ms=eager,
+           cpu_s=cpu_time(lambda: S.linear_relu_forward(Xc, Wc, bc)) if cpu else None, cpu_note=note)
+    dX = torch.empty(M, K, device=dev, dtype=bf); dW = torch.empty(N, K, device=dev, dtype=bf); db = torch.empty(N, device=dev)
+    ms = timeit(lambda: api.fdl_linear_relu_backward("bf16", dY, X, W, b, dX, dW, db, ws, st))
+    Xg = X.clone().requires_grad_(True); Wg_ = W.clone().requires_grad_(True); bg = bb.clone().requires_grad_(True)
+
+    def eager_bwd():
+        F.relu(F.linear(Xg, Wg_, bg)).backward(dY)
+        Xg.grad = Wg_.grad = bg.grad = None
+    eager = timeit(eager_bwd)     # forward + backward: eager keeps the forward's output for the mask
+    report("fdl_linear_relu_backward (recomputes the pre-activation: 3 contractions)", [M, K, N], ms, flop=6.0 * M * N * K,
+           eager_ms=eager, cpu_s=cpu_time(lambda: S.linear_relu_backward(dYc, Xc, Wc, bc)) if cpu else None, cpu_note=note)
+    del Xg, Wg_, dX, dW, ws
+
+    # LayerNorm / RMSNorm forward
+    A = (rnd(M, N) * 2 + 0.5).to(bf)
+    mean = torch.empty(M, device=dev); rstd = torch.empty(M, device=dev)
+    Ac = A[:rows].float().cpu().numpy()
+    ms = timeit(lambda: api.fdl_layernorm_forward("bf16", A, gm, bt, 1e-5, Y, mean, rstd, st))
+    eager = timeit(lambda: F.layer_norm(A, (N,), gg, btt, 1e-5))
+    report("fdl_layernorm_forward", [M, N], ms, nbytes=2.0 * M * N * 2, eager_ms=eager,
+           cpu_s=cpu_time(lambda: S.layernorm_forward(Ac, gc, btc, 1e-5)) if cpu else None, cpu_note=note)
+    ms = timeit(lambda: api.fdl_rmsnorm_forward("bf16", A, gm, 1e-5, Y, st))
+    eager = timeit(lambda: F.rms_norm(A, (N,), gg, 1e-5))
+    report("fdl_rmsnorm_forward", [M, N], ms, nbytes=2.0 * M * N * 2, eager_ms=eager,
+           cpu_s=cpu_time(lambda: S.rmsnorm_forward(Ac, gc, 1e-5)) if cpu else None, cpu_note=note)
+    del A, X, W, dY, Y
+
+    # Llama feed-forward block (7B-class widths)
+    Mt, D, Hd = 16384, 4096, 11008
+    X = rnd(Mt, D).to(bf); Wg = (rnd(Hd, D) / D ** 0.5).to(bf); Wu = (rnd(Hd, D) / D ** 0.5).to(bf); Wd = (rnd(D, Hd) / Hd ** 0.5).to(bf)
+    Y = torch.empty(Mt, D, device=dev, dtype=bf)
+    ws = torch.empty(api.fdl_llama_ffn_workspace_bytes("bf16", Mt, D, Hd), dtype=torch.uint8, device=dev)
+    ms = timeit(lambda: api.fdl_llama_ffn_forward("bf16", X, Wg, Wu, Wd, Y, ws, st))
+    eager = timeit(lambda: F.linear(F.silu(F.linear(X, Wg)) * F.linear(X, Wu), Wd))
+    r2 = 512
+    args = [t.float().cpu().numpy() for t in (X[:r2], Wg, Wu, Wd)]
+    report("fdl_llama_ffn_forward", [Mt, D, Hd], ms, flop=6.0 * Mt * D * Hd, eager_ms=eager,
+           cpu_s=cpu_time(lambda: S.llama_ffn_forward(*args)) if cpu else None, cpu_note=f"first {r2} of {Mt} rows, fp64 numpy")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -360,6 +463,8 @@ def main():
                     help="print the measured ceilings (MFMA loop, streaming, LDS access-pattern probes) as a text table")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference point for HBM byte counters)")
+    ap.add_argument("--siblings", action="store_true",
+                    help="time the forward-only entry point and the sibling operators (one JSON line each)")
     ap.add_argument("--sweep", action="store_true",
                     help="print a throughput table over tuned and untuned shapes instead of the JSON line")
     args = ap.parse_args()
@@ -380,6 +485,9 @@ def main():
         return
     if args.sweep:
         run_sweep(min(args.steps, 20), min(args.warmup, 5))
+        return
+    if args.siblings:
+        run_siblings(min(args.steps, 20), min(args.warmup, 5), not args.no_cpu_baseline)
         return
     cfg = I.CONFIGS[args.config]
     dev = torch.device("cuda:0")

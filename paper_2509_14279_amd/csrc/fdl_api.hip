@@ -84,18 +84,28 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   const size_t cs = dt == kF32 ? 8 : 4;   // arithmetic element
   Plan q = {};
   q.dt = dt; q.M = M; q.K = K; q.N = N;
+
+  // ---- which contraction kernels run
+  // bf16: the tuned kernel where N and K are multiples of the tile and the pipeline round (as they are), or - padded
+  // mode - merely multiples of 8: the kernels then run on N and K rounded up to the tile, on a zero-padded copy of
+  // the weights, and leave the surplus unstored.  Everything else takes the generic kernel.
+  q.pad = dt == kBF16 && fast_padded_supported(M, K, N);
+  const int64_t Np = q.pad ? fast_pad_dim(N) : N, Kp = q.pad ? fast_pad_dim(K) : K;
+  q.ldz = Np;
   const int64_t Mp = M > 0 ? M : 1;
+  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
 
   // ---- forward
-  q.f1_fast = dt == kBF16 && fast_f1_supported(M, K, N);
-  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  q.f1_fast = q.pad || (dt == kBF16 && fast_f1_supported(M, K, N));
   q.f2_rows = q.f1_fast && f2_rows_supported(dt, N);
   q.f1_wb = pick_wb(Mp, N);
   q.stat_tile_w = q.f1_fast ? fast_f1_stat_tile_w() : 16 * q.f1_wb;
   q.stat_tiles = (int)((N + q.stat_tile_w - 1) / q.stat_tile_w);
   size_t off = 0;
   q.off_part = off; off += align256(q.f2_rows ? 0 : (size_t)q.stat_tiles * Mp * 8);   // no partials where F2 takes the statistics
-  q.off_xtail = off; off += align256(q.f1_fast ? fast_f1_tail_bytes(M, K) : 0);
+  q.off_xtail = off; off += align256(q.pad ? fast_padded_tail_bytes(K) : (q.f1_fast ? fast_f1_tail_bytes(M, K) : 0));
+  q.off_wpad_f = off; off += align256(q.pad ? (size_t)Np * Kp * 2 : 0);
+  q.off_bpad_f = off; off += align256(q.pad ? (size_t)Np * 4 : 0);
   q.fwd_bytes = off;
 
   // ---- backward
@@ -110,20 +120,30 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
     q.b1_rows_per_group = (int)rpg;
     q.b1_groups = (int)((Mp + rpg - 1) / rpg);
   }
-  q.b3_fast = dt == kBF16 && fast_b3_supported(M, K, N);
-  q.b4_fast = dt == kBF16 && fast_b4_supported(M, K, N);
+  q.b3_fast = q.pad || (dt == kBF16 && fast_b3_supported(M, K, N));
   q.b3_wb = pick_wb(Mp, K);
   q.b4_wb = pick_wb(N, K);
-  q.b4_fast_rows = q.b4_fast ? fast_b4_rows(M) : 0;
+  if (q.pad) {
+    q.b4_fast_rows = fast_padded_b4_rows(M, K);
+    q.b4_fast = q.b4_fast_rows >= 128;
+    if (!q.b4_fast) q.b4_fast_rows = 0;
+  } else {
+    q.b4_fast = dt == kBF16 && fast_b4_supported(M, K, N);
+    q.b4_fast_rows = q.b4_fast ? fast_b4_rows(M) : 0;
+  }
   q.b4_split = q.b4_fast ? fast_b4_split(q.b4_fast_rows, K, N) : 1;
-  const int b4_parts = q.b4_split + (q.b4_fast && q.b4_fast_rows < M ? 1 : 0);   // fp32 partial sums of dW
+  // fp32 partial sums of dW: the parts of a split reduction, one more for the rows the fast kernel leaves to the
+  // generic one; in padded mode the fast kernel always writes partials
+  int b4_parts = q.b4_split + (q.b4_fast && q.b4_fast_rows < M ? 1 : 0);
+  if (q.pad && q.b4_fast && b4_parts < 2) b4_parts = 2;   // (a single part is still a partial: reduced into dW)
   off = 0;
   // dZ: the fast dX kernel reads whole 256-row tiles, so the buffer is rounded up (the surplus rows are never
   // written and never reach an output)
-  q.off_dz = off; off += align256((size_t)((Mp + 255) / 256 * 256) * N * ts);
+  q.off_dz = off; off += align256((size_t)((Mp + 255) / 256 * 256) * Np * ts);
   q.off_c12 = off; off += align256(q.b1_fused ? 0 : (size_t)2 * Mp * cs);
   q.off_colpart = off; off += align256((size_t)q.b1_groups * 3 * N * cs);
   q.off_dwpart = off; off += align256(b4_parts > 1 ? (size_t)b4_parts * N * K * 4 : 0);
+  q.off_wpad_b = off; off += align256(q.pad ? (size_t)Np * Kp * 2 : 0);
   q.bwd_bytes = off;
   q.bytes = q.fwd_bytes > q.bwd_bytes ? q.fwd_bytes : q.bwd_bytes;
   *p = q;
@@ -226,7 +246,12 @@ static fdl_status forward_launches(const Plan& p, const void* X, const void* W, 
   void* part = ws + p.off_part;
   {
     PhaseTimer t(FDL_PHASE_F1, s);
-    if (p.f1_fast) {
+    if (p.pad) {
+      void* Wp = ws + p.off_wpad_f;
+      float* bp = reinterpret_cast<float*>(ws + p.off_bpad_f);
+      launch_fast_pad_weights(K, N, W, b, Wp, bp, s);
+      launch_fast_f1_padded(M, K, N, X, Wp, bp, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
+    } else if (p.f1_fast) {
       launch_fast_f1(M, K, N, X, W, b, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
     } else {
       GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
@@ -333,11 +358,12 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   {
     PhaseTimer t(FDL_PHASE_B1, s);
     if (p.b1_fused) {
-      launch_b1_fused((int)dt, M, N, p.b1_groups, p.f2_rows != 0, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+      launch_b1_fused((int)dt, M, N, p.ldz, p.b1_groups, p.f2_rows != 0, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
     } else {
       launch_b1a((int)dt, M, N, dY, Zsave, gamma, mean, rstd, c12, s);
-      launch_b1b((int)dt, M, N, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+      launch_b1b((int)dt, M, N, p.ldz, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
     }
+    if (p.pad) launch_zero_cols_bf16(dZ, M, N, p.ldz, s);   // the surplus columns enter the dX and dW contractions
   }
   {
     PhaseTimer t(FDL_PHASE_B2, s);
@@ -346,17 +372,36 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   {
     // B3: dX[M,K] = dZ[M,N] W[N,K]
     PhaseTimer t(FDL_PHASE_B3, s);
-    if (p.b3_fast) {
+    if (p.pad) {
+      void* Wp = ws + p.off_wpad_b;
+      launch_fast_pad_weights(K, N, W, nullptr, Wp, nullptr, s);
+      launch_fast_b3_padded(M, K, N, dZ, Wp, dX, s);
+    } else if (p.b3_fast) {
       launch_fast_b3(M, K, N, dZ, W, dX, s);
     } else {
-      GemmDesc g = {dZ, W, M, K, N, N, K, true, false, p.b3_wb};
+      GemmDesc g = {dZ, W, M, K, N, p.ldz, K, true, false, p.b3_wb};
       launch_generic_store((int)dt, g, dX, s);
     }
   }
   {
     // B4: dW[N,K] = dZ^T[N,M] X[M,K]
     PhaseTimer t(FDL_PHASE_B4, s);
-    if (p.b4_fast) {
+    if (p.pad && p.b4_fast) {
+      // padded mode: the fast kernel writes fp32 partials of the first b4_fast_rows rows; the generic kernel adds one
+      // for the remaining rows (there is always at least one when K is not a multiple of the tile)
+      const int64_t Mf = p.b4_fast_rows;
+      float* dwpart = reinterpret_cast<float*>(ws + p.off_dwpart);
+      launch_fast_b4_padded(Mf, K, N, p.b4_split, dZ, X, dwpart, s);
+      int parts = p.b4_split;
+      if (Mf < M) {
+        const char* dZt = static_cast<const char*>(dZ) + (size_t)Mf * p.ldz * 2;
+        const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
+        GemmDesc g = {dZt, Xt, N, K, M - Mf, p.ldz, K, false, false, p.b4_wb};
+        launch_generic_store_f32(g, dwpart + (size_t)parts * N * K, s);
+        parts++;
+      }
+      launch_fast_b4_reduce(K, N, parts, dwpart, dW, s);
+    } else if (p.b4_fast) {
       // the fast kernel reduces over the first b4_fast_rows rows (a whole number of pipeline rounds); the few rows
       // after them go through the generic kernel into one more fp32 partial sum
       const int64_t Mf = p.b4_fast_rows;
@@ -371,7 +416,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
         launch_fast_b4_reduce(K, N, p.b4_split + 1, dwpart, dW, s);
       }
     } else {
-      GemmDesc g = {dZ, X, N, K, M, N, K, false, false, p.b4_wb};
+      GemmDesc g = {dZ, X, N, K, M, p.ldz, K, false, false, p.b4_wb};
       launch_generic_store((int)dt, g, dW, s);
     }
   }
@@ -430,18 +475,30 @@ namespace {
 // Workspace of the Linear+ReLU pair (one layout for both passes): the masked upstream gradient G [M][N] in the
 // storage type with rows padded to whole tiles (the fast dX kernel reads whole tiles), the first-stage column
 // partials of db, the fp32 partial sums of a split dW reduction, and the padded copy of X's last rows.
-struct ReluPlan { Plan p; size_t off_g, off_colpart, off_dwpart, off_xtail, bytes; };
+struct ReluPlan {
+  int f1_fast, b3_fast, b4_fast, b4_split, f1_wb, b3_wb, b4_wb;
+  int64_t b4_fast_rows;
+  size_t off_g, off_colpart, off_dwpart, off_xtail, bytes;
+};
 bool make_relu_plan(int dt, int64_t M, int64_t K, int64_t N, ReluPlan* q) {
-  if (!make_plan(dt, M, K, N, &q->p)) return false;
-  const Plan& p = q->p;
+  if (dt != kF32 && dt != kBF16) return false;
+  if (!shape_ok(M, K, N)) return false;
   const size_t ts = dt == kF32 ? 4 : 2, cs = dt == kF32 ? 8 : 4;
   const int64_t Mp = M > 0 ? M : 1;
-  const int b4_parts = p.b4_split + (p.b4_fast && p.b4_fast_rows < M ? 1 : 0);
+  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  // the tuned kernels where the shape fits their tiles and pipeline rounds as it is; the generic kernel otherwise
+  q->f1_fast = dt == kBF16 && fast_f1_supported(M, K, N);
+  q->b3_fast = dt == kBF16 && fast_b3_supported(M, K, N);
+  q->b4_fast = dt == kBF16 && fast_b4_supported(M, K, N);
+  q->b4_fast_rows = q->b4_fast ? fast_b4_rows(M) : 0;
+  q->b4_split = q->b4_fast ? fast_b4_split(q->b4_fast_rows, K, N) : 1;
+  q->f1_wb = pick_wb(Mp, N); q->b3_wb = pick_wb(Mp, K); q->b4_wb = pick_wb(N, K);
+  const int b4_parts = q->b4_split + (q->b4_fast && q->b4_fast_rows < M ? 1 : 0);
   size_t off = 0;
   q->off_g = off; off += align256((size_t)((Mp + 255) / 256 * 256) * N * ts);
   q->off_colpart = off; off += align256((size_t)colsum_groups(Mp) * N * cs);
   q->off_dwpart = off; off += align256(b4_parts > 1 ? (size_t)b4_parts * N * K * 4 : 0);
-  q->off_xtail = off; off += align256(p.f1_fast ? fast_f1_tail_bytes(M, K) : 0);
+  q->off_xtail = off; off += align256(q->f1_fast ? fast_f1_tail_bytes(M, K) : 0);
   q->bytes = off;
   return true;
 }
@@ -472,10 +529,10 @@ extern "C" fdl_status fdl_linear_relu_forward(fdl_dtype dt, int64_t M, int64_t K
   clear_stale_error();
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
-  if (q.p.f1_fast) {
+  if (q.f1_fast) {
     launch_fast_xwt(1, M, K, N, X, false, W, b, nullptr, Y, ws + q.off_xtail, s);
   } else {
-    GemmDesc g = {X, W, M, N, K, K, K, true, true, q.p.f1_wb};
+    GemmDesc g = {X, W, M, N, K, K, K, true, true, q.f1_wb};
     launch_generic_xwt((int)dt, 1, g, b, nullptr, Y, s);
   }
   return launch_status();
@@ -495,7 +552,7 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
     return FDL_ERR_ALIGN;
   clear_stale_error();
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const Plan& p = q.p;
+  const ReluPlan& p = q;
   if (M == 0) {
     const int64_t nk = N * K;
     if (dt == FDL_F32) hipLaunchKernelGGL(zero_f32_kernel, dim3(256), dim3(256), 0, s, (float*)dW, nk);

@@ -214,13 +214,19 @@ __device__ __forceinline__ TileCoord tile_coord(int L, int tiles_i, int tiles_j)
   return c;
 }
 
-// RAG: the number of output rows J is not a multiple of the tile (ragged batch dimension of F1 and B3).  The last
-// row tile then reads its Q rows from a padded copy (or from a Q buffer that is itself padded), computes the
-// surplus rows on whatever that padding holds - rows of a product are independent - and does not store them.
-template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG>
+// RAG: the number of output rows J is not a multiple of the tile (ragged batch dimension of F1 and B3, ragged N of
+// B4).  The last row tile then reads its Q rows from a padded copy (or from a Q buffer that is itself padded), computes
+// the surplus rows on whatever that padding holds - rows of a product are independent - and does not store them.
+// CRAG (with RAG): the number of output columns I is a multiple of 8 but not of the tile.  The host hands over a P
+// operand that is readable up to the end of the last column tile (a zero-padded copy of the weights, or a matrix
+// whose surplus columns are the start of its next row) and a bias padded likewise; the surplus columns are computed
+// and not stored, and are left out of the row statistics where the epilogue takes them.
+// A reduction length that is not a whole number of pipeline rounds is the host's business as well: it rounds the
+// length up and makes one operand zero over the surplus (the other only has to be readable and finite there).
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG, bool CRAG = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void gemm_bf16_kernel(FastParams p) {
-  static_assert(!RAG || !Q_RM, "a ragged row count is supported for r-contiguous Q only");
+  static_assert(!CRAG || RAG, "ragged columns come with the ragged-row checks");
   typedef Geo<BK> G;
   static_assert(NS * G::kStageBytes == kLdsStages, "stages must fill 128 KB");
   static_assert((NS == 2 || NS == 4) && (G::kSub & 1) == 0, "2 or 4 stages, even number of sub-slices");
@@ -271,7 +277,7 @@ void gemm_bf16_kernel(FastParams p) {
     return lp.wave_base(P_RM ? p.P + r_begin * p.ldp + i0 : p.P + (int64_t)i0 * p.ldp + r_begin, p.ldp, wave);
   };
   auto q_origin = [&](int j0) {
-    if (RAG && p.Qtail != nullptr && j0 == (p.tiles_j - 1) * kTile) return lq.wave_base(p.Qtail + r_begin, p.ldq, wave);
+    if (RAG && !Q_RM && p.Qtail != nullptr && j0 == (p.tiles_j - 1) * kTile) return lq.wave_base(p.Qtail + r_begin, p.ldq, wave);
     return lq.wave_base(Q_RM ? p.Q + r_begin * p.ldq + j0 : p.Q + (int64_t)j0 * p.ldq + r_begin, p.ldq, wave);
   };
 
@@ -505,6 +511,7 @@ void gemm_bf16_kernel(FastParams p) {
         const u32x4 v = *(const lds_u32x4*)(wtile + roff[it & 3] + (it >> 2) * 4096);
         u32x4* dst = reinterpret_cast<u32x4*>(cbase + (int64_t)(it * 4) * p.I * 2 + svoff);
         if (RAG && j0 + wj * 128 + b * 32 + it * 4 + e_rq >= p.J) continue;   // a row past the end
+        if (CRAG && i0 + wi * 128 + e_m * 8 >= p.I) continue;                  // 8 columns past the end
         if (EPI == EPI_MASK) {
           // v: 8 pre-activations as bf16.  The upstream gradient passes where the pre-activation is positive (bits
           // 0x0001 .. 0x7fff: sign clear, magnitude non-zero) and is zero elsewhere.
@@ -540,6 +547,8 @@ void gemm_bf16_kernel(FastParams p) {
             f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; e++) v[e] = acc[a][b][g * 4 + e];
+            if (RAG && j0 + wj * 128 + b * 32 + e_l32 >= p.J) continue;                          // a row past the end
+            if (CRAG && i0 + wi * 128 + a * 32 + g * 8 + e_half * 4 >= p.I) continue;            // 4 columns past the end
             *reinterpret_cast<f32x4*>(obase + (a * 32 + g * 8) * 4 + pvoff) = v;
           }
         __builtin_amdgcn_sched_barrier(0);
@@ -566,6 +575,10 @@ void gemm_bf16_kernel(FastParams p) {
       // Z (bias included) rounded to bf16 and stored; A = GELU(stored Z); per output row j, mean and sum of squared
       // deviations of A over this wave's 128 columns: 64 values in the lane, 64 in lane ^ 32.
       const int stat_tile = (i0 + wi * 128) >> 7;
+      // CRAG: columns of this wave's 128 that exist (a multiple of 4, wave-uniform); the others are masked out
+      int nvalid = 128;
+      if (CRAG) { nvalid = p.I - (i0 + wi * 128); nvalid = nvalid < 0 ? 0 : (nvalid > 128 ? 128 : nvalid); }
+      const float inv_valid = 1.0f / (float)(nvalid > 0 ? nvalid : 1);
 #pragma unroll
       for (int b = 0; b < 4; b++) {
         const int64_t j = jw + b * 32;
@@ -575,27 +588,29 @@ void gemm_bf16_kernel(FastParams p) {
 #pragma unroll
           for (int g = 0; g < 4; g++) {
             bf16x4 zs;
+            const bool live = !CRAG || a * 32 + g * 8 + e_half * 4 < nvalid;
 #pragma unroll
             for (int e = 0; e < 4; e++) {
               zs[e] = (bf16_t)acc[a][b][g * 4 + e];
-              const float act = gelu<float>((float)zs[e]);
+              const float act = live ? gelu<float>((float)zs[e]) : 0.0f;
               acc[a][b][g * 4 + e] = act;
               sum += act;
             }
             *(lds_bf16x4*)(wtile + woff[a][g]) = zs;
           }
         sum += __shfl_xor(sum, 32, kWave);
-        const float mean = sum * (1.0f / 128.0f);
+        const float mean = sum * inv_valid;
         float m2 = 0.0f;
 #pragma unroll
         for (int a = 0; a < 4; a++)
 #pragma unroll
           for (int r = 0; r < 16; r++) {
-            const float d = acc[a][b][r] - mean;
+            const bool live = !CRAG || a * 32 + (r >> 2) * 8 + e_half * 4 < nvalid;
+            const float d = live ? acc[a][b][r] - mean : 0.0f;
             m2 = __builtin_fmaf(d, d, m2);
           }
         m2 += __shfl_xor(m2, 32, kWave);
-        if (e_half == 0 && (!RAG || j < p.J)) {
+        if (e_half == 0 && (!RAG || j < p.J) && (!CRAG || nvalid > 0)) {
           f32x2 o; o[0] = mean; o[1] = m2;
           p.part[(int64_t)stat_tile * p.J + j] = o;
         }
@@ -625,10 +640,12 @@ __global__ __launch_bounds__(256) void reduce_split_kernel(const float* __restri
   *reinterpret_cast<bf16x4*>(out + i) = o;
 }
 
-// Padded copy of the rows [row0, rows) of a row-major matrix: 256 rows, zeros past the end.
+// Padded copy of the rows [row0, rows) of a row-major matrix: rows_out rows of the same pitch, zeros past the end.
+// (256 rows for a ragged row count; one more where the kernel also reads past the end of every row - a reduction
+// length rounded up - so that the last row's surplus stays inside the copy.)
 __global__ __launch_bounds__(256) void copy_tail_rows_kernel(const bf16_t* __restrict__ src, int64_t rows, int64_t ld,
-                                                             int64_t row0, bf16_t* __restrict__ dst) {
-  const int64_t n8 = (int64_t)kTile * ld / 8;   // ld is a multiple of 8 on this path
+                                                             int64_t row0, bf16_t* __restrict__ dst, int rows_out) {
+  const int64_t n8 = (int64_t)rows_out * ld / 8;   // ld is a multiple of 8 on this path
   for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += (int64_t)gridDim.x * 256) {
     const int64_t r = (v * 8) / ld;
     u32x4 x = {0u, 0u, 0u, 0u};
@@ -637,10 +654,27 @@ __global__ __launch_bounds__(256) void copy_tail_rows_kernel(const bf16_t* __res
   }
 }
 
-template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG = false>
+// Zero-padded copy of a row-major matrix: dst [rows_out][cols_out] = src [rows][cols] (cols, cols_out multiples of 8).
+__global__ __launch_bounds__(256) void pad_matrix_kernel(const bf16_t* __restrict__ src, int64_t rows, int64_t cols,
+                                                         bf16_t* __restrict__ dst, int64_t rows_out, int64_t cols_out) {
+  const int64_t vpr = cols_out / 8, n8 = rows_out * vpr;
+  for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < n8; v += (int64_t)gridDim.x * 256) {
+    const int64_t r = v / vpr, c = (v - r * vpr) * 8;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (r < rows && c < cols) x = *reinterpret_cast<const u32x4*>(src + r * cols + c);
+    *reinterpret_cast<u32x4*>(dst + r * cols_out + c) = x;
+  }
+}
+__global__ __launch_bounds__(256) void pad_vector_kernel(const float* __restrict__ src, int64_t n, float* __restrict__ dst,
+                                                         int64_t n_out) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_out; i += (int64_t)gridDim.x * 256)
+    dst[i] = i < n ? src[i] : 0.0f;
+}
+
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG = false, bool CRAG = false>
 void launch(FastParams p, hipStream_t s) {
   static OnceFlags configured;   // the dynamic LDS limit is raised once per kernel and device
-  auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI, BK, NS, RAG>;
+  auto kern = gemm_bf16_kernel<P_RM, Q_RM, EPI, BK, NS, RAG, CRAG>;
   if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kLdsBytes, &configured)) return;
   DeviceInfo di;
   if (!device_info(&di)) return;
@@ -693,6 +727,42 @@ bool fast_b4_supported(int64_t M, int64_t K, int64_t N) {
 int fast_f1_stat_tile_w() { return 128; }
 size_t fast_f1_tail_bytes(int64_t M, int64_t K) { return M % kTile ? (size_t)kTile * K * 2 : 0; }
 
+// ---- padded mode: N and K multiples of 8 (16-byte rows) but not both multiples of the tile ----------------------
+// The contractions then run on the same kernels with N and K rounded up to the tile: the weights are copied into a
+// zero-padded [Np][Kp] matrix (small: it is the only operand that is copied whole), the bias into a padded vector,
+// dZ is laid out with pitch Np and zero surplus columns, and the kernels leave the surplus output columns and rows
+// unstored.  Where X is read past the end of its rows (K rounded up: forward) the surplus is the start of X's next
+// row times the weights' zero padding; only X's last row has no next row, so the forward pass takes its last row tile
+// from a copy with one spare row.
+int64_t fast_pad_dim(int64_t n) { return (n + kTile - 1) / kTile * kTile; }
+bool fast_padded_supported(int64_t M, int64_t K, int64_t N) {
+  // K >= 128: a row read up to the rounded-up K then ends inside the next row (Kp <= 2 K), which is what keeps those
+  // reads inside X (every row the kernels read that way has a successor) and inside the copy of X's last rows
+  if (M < kMinRaggedRows || N < 8 || K < 128 || N % 8 || K % 8) return false;
+  if (N % kTile == 0 && K % kTile == 0) return false;     // nothing to pad: the plain fast path applies
+  const int64_t Np = fast_pad_dim(N), Kp = fast_pad_dim(K), tj = (M + kTile - 1) / kTile;
+  return Np <= (1 << 24) && Kp <= (1 << 24) && M <= (1 << 24) && (Np / kTile) * tj <= (1 << 30) && (Kp / kTile) * tj <= (1 << 30) &&
+         (Np / kTile) * (Kp / kTile) <= (1 << 30);
+}
+size_t fast_padded_tail_bytes(int64_t K) { return (size_t)(kTile + 1) * K * 2; }
+// rows of the dW reduction the fast kernel covers in padded mode: where X is read past the end of its rows (K rounded
+// up) the last row it touches must have a successor
+int64_t fast_padded_b4_rows(int64_t M, int64_t K) {
+  const int64_t u = (int64_t)kB4BK * stages_of(kB4BK);
+  return (K % kTile ? M - 1 : M) / u * u;
+}
+
+// Wp [Np][Kp] and biasp [Np] (biasp and bias may be null) from W [N][K] and bias [N]
+void launch_fast_pad_weights(int64_t K, int64_t N, const void* W, const float* bias, void* Wp, float* biasp, hipStream_t s) {
+  const int64_t Np = fast_pad_dim(N), Kp = fast_pad_dim(K);
+  const int64_t n8 = Np * Kp / 8;
+  int64_t blocks = (n8 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(pad_matrix_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (const bf16_t*)W, N, K, (bf16_t*)Wp, Np, Kp);
+  if (biasp != nullptr)
+    hipLaunchKernelGGL(pad_vector_kernel, dim3((unsigned)((Np + 255) / 256)), dim3(256), 0, s, bias, N, biasp, Np);
+}
+
 // part != nullptr: also emit the per-(row, 128-column tile) partial statistics of GELU(Zsave).
 // xtail: fast_f1_tail_bytes(M, K) bytes of scratch for the padded copy of X's last rows (M not a multiple of 256)
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
@@ -705,13 +775,30 @@ void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* 
   if (M % kTile) {
     p.Qtail = (const bf16_t*)xtail;
     hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, K,
-                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail);
+                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail, kTile);
     if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK), true>(p, s);
     else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK), true>(p, s);
   } else {
     if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK)>(p, s);
     else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK)>(p, s);
   }
+}
+
+// Padded mode: Wp [Np][Kp], biasp [Np] from launch_fast_pad_weights; xtail: fast_padded_tail_bytes(K) bytes
+void launch_fast_f1_padded(int64_t M, int64_t K, int64_t N, const void* X, const void* Wp, const float* biasp, void* Zsave,
+                           void* part, void* xtail, hipStream_t s) {
+  const int64_t Np = fast_pad_dim(N), Kp = fast_pad_dim(K);
+  FastParams p = {};
+  p.P = (const bf16_t*)Wp; p.Q = (const bf16_t*)X; p.ldp = Kp; p.ldq = K;
+  p.C = (bf16_t*)Zsave; p.bias = biasp; p.part = (f32x2*)part;
+  p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(Np / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
+  p.nkt = (int)(Kp / kF1BK); p.split = 1;
+  // the last row tile always comes from the copy: its rows are read up to Kp columns, and X's last row has no successor
+  p.Qtail = (const bf16_t*)xtail;
+  hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, K,
+                     (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail, kTile + 1);
+  if (part != nullptr) launch<false, false, EPI_F1, kF1BK, stages_of(kF1BK), true, true>(p, s);
+  else launch<false, false, EPI_BIAS, kF1BK, stages_of(kF1BK), true, true>(p, s);
 }
 
 // out[m][n] = f(sum_k X[m][k] W[n][k] + bias[n]) for the sibling operators; same shape rules as launch_fast_f1.
@@ -730,7 +817,7 @@ void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, b
   if (rag && !x_padded) {
     p.Qtail = (const bf16_t*)xtail;
     hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, K,
-                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail);
+                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail, kTile);
   }
   constexpr int NS = stages_of(kF1BK);
 #define FDL_XWT(EPI)                                                              \
@@ -756,9 +843,20 @@ void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void*
   else launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK)>(p, s);
 }
 
+// Padded mode: dZ [.][Np] with zero surplus columns and readable rows up to the next multiple of 256; Wp [Np][Kp]
+void launch_fast_b3_padded(int64_t M, int64_t K, int64_t N, const void* dZ, const void* Wp, void* dX, hipStream_t s) {
+  const int64_t Np = fast_pad_dim(N), Kp = fast_pad_dim(K);
+  FastParams p = {};
+  p.P = (const bf16_t*)Wp; p.Q = (const bf16_t*)dZ; p.ldp = Kp; p.ldq = Np;
+  p.C = (bf16_t*)dX;
+  p.I = (int)K; p.J = (int)M; p.tiles_i = (int)(Kp / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
+  p.nkt = (int)(Np / kB3BK); p.split = 1;
+  launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK), true, true>(p, s);
+}
+
 // Split of the reduction over M so that small dW outputs still fill the chip: each part keeps >= 512 rows.
 int fast_b4_split(int64_t M, int64_t K, int64_t N) {
-  const int64_t tiles = (K / kTile) * (N / kTile);
+  const int64_t tiles = ((K + kTile - 1) / kTile) * ((N + kTile - 1) / kTile);
   const int64_t unit = (int64_t)kB4BK * stages_of(kB4BK);   // every part is a whole number of slice groups
   int split = 1;
   while (tiles * split * 2 <= kPlanCUs && M % (split * 2 * unit) == 0 && M / (split * 2) >= 512) split *= 2;
@@ -778,6 +876,20 @@ void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const
   if (split > 1 || extra > 0) launch<true, true, EPI_PARTIAL, kB4BK, stages_of(kB4BK)>(p, s);
   else launch<true, true, EPI_STORE, kB4BK, stages_of(kB4BK)>(p, s);
   if (split > 1 && extra == 0) launch_fast_b4_reduce(K, N, split, dwpart, dW, s);
+}
+
+// Padded mode: dZ has pitch Np (zero surplus columns); X is read up to Kp columns per row, so M must be at most
+// fast_padded_b4_rows.  Always writes fp32 partial sums dwpart[0 .. split) (pitch K, surplus rows and columns unstored);
+// the caller adds what it must and calls launch_fast_b4_reduce.
+void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dwpart,
+                           hipStream_t s) {
+  const int64_t Np = fast_pad_dim(N), Kp = fast_pad_dim(K);
+  FastParams p = {};
+  p.P = (const bf16_t*)X; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = Np;
+  p.C = nullptr; p.Cpart = (float*)dwpart;
+  p.I = (int)K; p.J = (int)N; p.tiles_i = (int)(Kp / kTile); p.tiles_j = (int)(Np / kTile);
+  p.nkt = (int)(M / kB4BK / split); p.split = split;
+  launch<true, true, EPI_PARTIAL, kB4BK, stages_of(kB4BK), true, true>(p, s);
 }
 
 void launch_fast_b4_reduce(int64_t K, int64_t N, int parts, const void* dwpart, void* dW, hipStream_t s) {

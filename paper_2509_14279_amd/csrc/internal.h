@@ -39,6 +39,10 @@ struct Plan {
   int b3_wb, b4_wb;
   int b4_split;           // split of the reduction over M in B4 (fast kernel)
   int64_t b4_fast_rows;   // rows of the reduction the fast kernel covers (the rest goes through the generic kernel)
+  int pad;                // 1: padded mode of the fast contractions (N, K multiples of 8, not both of 256)
+  int64_t ldz;            // pitch of the dZ buffer in elements (N, or N rounded up to 256 in padded mode)
+  size_t off_wpad_f, off_bpad_f;   // forward: zero-padded copies of W [Np][Kp] and b [Np]
+  size_t off_wpad_b;               // backward: zero-padded copy of W
   size_t off_xtail;       // forward: padded copy of X's last rows (ragged M on the fast path)
   size_t off_dz;          // T [M][N]
   size_t off_c12;         // C [2][M]
@@ -97,14 +101,16 @@ void launch_f2_rows(int64_t M, int64_t N, float eps, const void* Zsave, const fl
                     float* mean, float* rstd, hipStream_t s);
 void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave, const float* gamma,
                 const float* mean, const float* rstd, void* c12, hipStream_t s);
-void launch_b1b(int dt, int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Zsave,
+// ldz: pitch of dZ in elements (N, or N rounded up to the tile in the padded mode of the fast contractions)
+void launch_b1b(int dt, int64_t M, int64_t N, int64_t ldz, int rows_per_group, int groups, const void* dY, const void* Zsave,
                 const float* gamma, const float* mean, const float* rstd, const void* c12, void* dZ,
                 void* colpart, hipStream_t s);
 // fused single pass (row held in registers); returns false if this N is not supported by it
 bool b1_fused_supported(int dt, int64_t N);
 int b1_fused_groups(int dt, int64_t N);   // number of row groups it should be launched with (before capping at M)
 // table: evaluate GELU from the LDS table, as the forward pass did (bf16, plan.f2_rows); else as the other kernels do
-void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, bool table, const void* dY, const void* Zsave,
+void launch_zero_cols_bf16(void* dZ, int64_t M, int64_t N, int64_t ldz, hipStream_t s);
+void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, const void* dY, const void* Zsave,
                      const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart,
                      hipStream_t s);
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
@@ -129,6 +135,17 @@ int fast_f1_stat_tile_w();
 size_t fast_f1_tail_bytes(int64_t M, int64_t K);
 void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
                     void* part, void* xtail, hipStream_t s);
+// padded mode (N, K multiples of 8 but not both of 256): see gemm_bf16.hip
+bool fast_padded_supported(int64_t M, int64_t K, int64_t N);
+int64_t fast_pad_dim(int64_t n);
+size_t fast_padded_tail_bytes(int64_t K);
+int64_t fast_padded_b4_rows(int64_t M, int64_t K);
+void launch_fast_pad_weights(int64_t K, int64_t N, const void* W, const float* bias, void* Wp, float* biasp, hipStream_t s);
+void launch_fast_f1_padded(int64_t M, int64_t K, int64_t N, const void* X, const void* Wp, const float* biasp, void* Zsave,
+                           void* part, void* xtail, hipStream_t s);
+void launch_fast_b3_padded(int64_t M, int64_t K, int64_t N, const void* dZ, const void* Wp, void* dX, hipStream_t s);
+void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dwpart,
+                           hipStream_t s);
 // sibling operators on the forward product's kernel (see gemm_bf16.hip); shapes as fast_f1_supported
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
                      const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);

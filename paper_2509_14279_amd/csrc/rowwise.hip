@@ -284,7 +284,7 @@ __global__ __launch_bounds__(256) void b1a_kernel(int64_t M, int64_t N, const T*
 
 // B1b (two-kernel path): dZ and column partials, given c1 and c2.
 template <class T, int V>
-__global__ __launch_bounds__(256) void b1b_kernel(int64_t M, int64_t N, int rows_per_group, int strips,
+__global__ __launch_bounds__(256) void b1b_kernel(int64_t M, int64_t N, int64_t ldz, int rows_per_group, int strips,
                                                   const T* __restrict__ dY, const T* __restrict__ Z,
                                                   const float* __restrict__ gamma, const float* __restrict__ mean,
                                                   const float* __restrict__ rstd,
@@ -318,7 +318,7 @@ __global__ __launch_bounds__(256) void b1b_kernel(int64_t M, int64_t N, int rows
       accg[v] += dy[v] * ah;
       accz[v] += dz[v];
     }
-    VecIO<T, V>::store(dZ + r * N + col, dz);
+    VecIO<T, V>::store(dZ + r * ldz + col, dz);
   }
 #pragma unroll
   for (int v = 0; v < V; v++) {
@@ -357,7 +357,7 @@ template <class T, int V> __device__ __forceinline__ typename RawVec<T, V>::type
 // mean and rstd did - for a constant row, rstd = eps^-1/2 multiplies any difference between the two into Ahat -
 // so the launcher selects TAB if and only if the forward pass normalised with the table.
 template <class T, int V, int S, int NT, bool TAB>
-__global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, const T* __restrict__ dY,
+__global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int64_t ldz, const T* __restrict__ dY,
                                                        const T* __restrict__ Z, const float* __restrict__ gamma,
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
                                                        T* __restrict__ dZ,
@@ -450,7 +450,7 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, cons
       if (ok[s]) {
         typename RawVec<T, V>::type o;
         if constexpr (V == 1) o = to_storage<T, C>(dz[0]); else { for (int v = 0; v < V; v++) o[v] = to_storage<T, C>(dz[v]); }
-        __builtin_nontemporal_store(o, reinterpret_cast<typename RawVec<T, V>::type*>(dZ + row * N + col[s]));
+        __builtin_nontemporal_store(o, reinterpret_cast<typename RawVec<T, V>::type*>(dZ + row * ldz + col[s]));
       }
     }
   };
@@ -636,19 +636,19 @@ template <class T> void b1a_impl(int64_t M, int64_t N, const void* dY, const voi
                        rstd, (C*)c12);
 }
 
-template <class T> void b1b_impl(int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Z,
+template <class T> void b1b_impl(int64_t M, int64_t N, int64_t ldz, int rows_per_group, int groups, const void* dY, const void* Z,
                                  const float* gamma, const float* mean, const float* rstd, const void* c12, void* dZ,
                                  void* colpart, hipStream_t s) {
   typedef typename ComputeOf<T>::type C;
   constexpr int VMAX = 16 / (int)sizeof(T);
-  const int V = vec_width<T>(dY, Z, dZ, N);
+  const int V = (ldz % VMAX == 0) ? vec_width<T>(dY, Z, dZ, N) : 1;
   const int strips = (int)((N + 256 * (int64_t)V - 1) / (256 * (int64_t)V));
   const int64_t blocks = (int64_t)strips * groups;
   if (V == VMAX)
-    hipLaunchKernelGGL((b1b_kernel<T, VMAX>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_group, strips,
+    hipLaunchKernelGGL((b1b_kernel<T, VMAX>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, ldz, rows_per_group, strips,
                        (const T*)dY, (const T*)Z, gamma, mean, rstd, (const C*)c12, (T*)dZ, (C*)colpart);
   else
-    hipLaunchKernelGGL((b1b_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_group, strips,
+    hipLaunchKernelGGL((b1b_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, ldz, rows_per_group, strips,
                        (const T*)dY, (const T*)Z, gamma, mean, rstd, (const C*)c12, (T*)dZ, (C*)colpart);
 }
 
@@ -664,7 +664,7 @@ inline bool fused_shape(int64_t N, int V, bool vec, FusedShape* out) {
   return false;
 }
 
-template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int groups, const void* dY, const void* Z,
+template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int64_t ldz, int groups, const void* dY, const void* Z,
                                                 const float* gamma, const float* mean, const float* rstd, void* dZ,
                                                 void* colpart, hipStream_t s) {
   typedef typename ComputeOf<T>::type C;
@@ -673,7 +673,7 @@ template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int groups
   FusedShape fs;
   if (!fused_shape(N, V, V == VMAX, &fs)) return;   // callers check b1_fused_supported first
 #define FDL_B1F(VV, SS, NTT)                                                                                       \
-  hipLaunchKernelGGL((b1_fused_kernel<T, VV, SS, NTT, TAB>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N,           \
+  hipLaunchKernelGGL((b1_fused_kernel<T, VV, SS, NTT, TAB>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N, ldz,      \
                      (const T*)dY, (const T*)Z, gamma, mean, rstd, (T*)dZ, (C*)colpart)
   if (V == VMAX) {
     if (fs.nt == 256) FDL_B1F(VMAX, 1, 256); else if (fs.nt == 512) FDL_B1F(VMAX, 1, 512); else FDL_B1F(VMAX, 1, 1024);
@@ -817,11 +817,28 @@ void launch_b1a(int dt, int64_t M, int64_t N, const void* dY, const void* Zsave,
   else b1a_impl<bf16_t>(M, N, dY, Zsave, gamma, mean, rstd, c12, s);
 }
 
-void launch_b1b(int dt, int64_t M, int64_t N, int rows_per_group, int groups, const void* dY, const void* Zsave,
+void launch_b1b(int dt, int64_t M, int64_t N, int64_t ldz, int rows_per_group, int groups, const void* dY, const void* Zsave,
                 const float* gamma, const float* mean, const float* rstd, const void* c12, void* dZ, void* colpart,
                 hipStream_t s) {
-  if (dt == kF32) b1b_impl<float>(M, N, rows_per_group, groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
-  else b1b_impl<bf16_t>(M, N, rows_per_group, groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+  if (dt == kF32) b1b_impl<float>(M, N, ldz, rows_per_group, groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+  else b1b_impl<bf16_t>(M, N, ldz, rows_per_group, groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
+}
+
+// dZ [M][ldz]: zero the surplus columns [N, ldz) of every row (padded mode of the fast contractions)
+namespace {
+__global__ __launch_bounds__(256) void zero_cols_kernel(unsigned short* __restrict__ dZ, int64_t M, int64_t N, int64_t ldz) {
+  const int64_t w = ldz - N, n = M * w;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t r = i / w, c = i - r * w;
+    dZ[r * ldz + N + c] = 0;
+  }
+}
+}  // namespace
+void launch_zero_cols_bf16(void* dZ, int64_t M, int64_t N, int64_t ldz, hipStream_t s) {
+  if (ldz <= N || M <= 0) return;
+  int64_t blocks = (M * (ldz - N) + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(zero_cols_kernel, dim3((unsigned)blocks), dim3(256), 0, s, (unsigned short*)dZ, M, N, ldz);
 }
 
 // Whether rows can be read with full-width vectors depends on N only here (base pointers are required to be
@@ -844,11 +861,11 @@ int b1_fused_groups(int dt, int64_t N) {
   return fs.nt == 1024 ? 256 : 512;
 }
 
-void launch_b1_fused(int dt, int64_t M, int64_t N, int groups, bool table, const void* dY, const void* Zsave,
+void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, const void* dY, const void* Zsave,
                      const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart, hipStream_t s) {
-  if (dt == kF32) b1_fused_impl<float, false>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
-  else if (table) b1_fused_impl<bf16_t, true>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
-  else b1_fused_impl<bf16_t, false>(M, N, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  if (dt == kF32) b1_fused_impl<float, false>(M, N, ldz, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else if (table) b1_fused_impl<bf16_t, true>(M, N, ldz, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else b1_fused_impl<bf16_t, false>(M, N, ldz, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
 }
 
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,

@@ -110,8 +110,16 @@ def test_small_and_ragged_shapes(dtype, shape):
     # epilogue for the long rows
     ("bf16", (300, 256, 512)), ("bf16", (1000, 256, 768)), ("bf16", (130, 256, 256)), ("bf16", (385, 512, 1024)),
     ("bf16", (129, 256, 8448)), ("bf16", (2500, 256, 2048)),
-    # reduction lengths that are not a whole number of pipeline rounds fall back to the generic GEMM per contraction
-    ("bf16", (256, 64, 512)), ("bf16", (320, 192, 256)),
+    # K below 128 or not a multiple of 8: the generic GEMM
+    ("bf16", (256, 64, 512)), ("bf16", (320, 100, 256)),
+    # padded mode of the tuned kernels: N and K multiples of 8 but not both of 256 - surplus output columns and rows
+    # unstored, weights copied zero-padded, dZ with a padded pitch; with a ragged M on top; with rows longer than the
+    # row-resident normalisation (statistics from the GEMM epilogue, masked at the ragged edge: 8200, 8456); with so
+    # few rows that dW falls to the generic kernel on the padded dZ (128, 200); N far below one tile (8, 64)
+    ("bf16", (320, 192, 256)), ("bf16", (512, 136, 520)), ("bf16", (2500, 1000, 3000)), ("bf16", (300, 200, 264)),
+    ("bf16", (129, 136, 256)), ("bf16", (128, 128, 264)), ("bf16", (200, 248, 2056)), ("bf16", (256, 384, 8200)),
+    ("bf16", (385, 256, 8456)), ("bf16", (1024, 1000, 8)), ("bf16", (2048, 1024, 64)), ("bf16", (640, 128, 1000)),
+    ("bf16", (4096, 520, 768)), ("bf16", (1500, 768, 776)),
 ])
 def test_aligned_and_long_row_shapes(dtype, shape):
     M, K, N = shape

@@ -40,7 +40,8 @@ def test_forward_static_matches_forward_on_two_calls_in_a_row():
     # first the larger problem, then smaller ones that reuse (part of) the same scratch bytes
     cases = [I.custom("bf16", 385, 512, 8448, seed=51),     # fast path, ragged M (padded X tail) + epilogue partials
              I.custom("f32", 130, 70, 200, seed=52),        # generic kernel partials, smaller
-             I.custom("bf16", 300, 256, 512, seed=53)]      # fast path, ragged M, row-resident normalisation
+             I.custom("bf16", 300, 256, 512, seed=53),      # fast path, ragged M, row-resident normalisation
+             I.custom("bf16", 200, 136, 264, seed=54)]      # padded mode: zero-padded weight copy + X tail in the scratch
     inputs = [I.generate(c, with_dY=False) for c in cases]
     got = []
     for c, t in zip(cases, inputs):                          # the static calls back to back, nothing in between
