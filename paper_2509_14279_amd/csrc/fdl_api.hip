@@ -632,8 +632,10 @@ extern "C" fdl_status fdl_rmsnorm_forward(fdl_dtype dt, int64_t M, int64_t N, co
 // ---- Llama feed-forward block, forward -----------------------------------------------------------------------------
 namespace {
 // Workspace: G and U [Mpad][H] in the storage type (the activation overwrites G; rows padded to whole tiles so that the
-// down projection's fast kernel may read a partial last row tile), then the padded copy of X's last rows.
+// down projection's fast kernel may read a partial last row tile; U only where the two products are separate kernels),
+// then the padded copy of X's last rows.
 struct FfnPlan {
+  int gate_fused;          // 1: one kernel forms both products and the gated activation (no M x H round trip)
   int up_fast, down_fast, up_wb, down_wb;
   size_t off_g, off_u, off_xtail, bytes;
 };
@@ -644,6 +646,7 @@ bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   const size_t ts = dt == kF32 ? 4 : 2;
   const int64_t Mp = M > 0 ? M : 1;
   auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  q->gate_fused = dt == kBF16 && fast_gate_supported(M, D, H);
   q->up_fast = dt == kBF16 && fast_f1_supported(M, D, H);      // [M,D] x [H,D]^T
   q->down_fast = dt == kBF16 && fast_f1_supported(M, H, D);    // [M,H] x [D,H]^T
   q->up_wb = pick_wb(Mp, H);
@@ -651,8 +654,8 @@ bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   size_t off = 0;
   const size_t mh = align256((size_t)((Mp + 255) / 256 * 256) * H * ts);
   q->off_g = off; off += mh;
-  q->off_u = off; off += mh;
-  q->off_xtail = off; off += align256(q->up_fast ? fast_f1_tail_bytes(M, D) : 0);
+  q->off_u = off; off += q->gate_fused ? 0 : mh;    // the fused kernel never materialises the up product
+  q->off_xtail = off; off += align256((q->up_fast || q->gate_fused) ? fast_f1_tail_bytes(M, D) : 0);
   q->bytes = off;
   return true;
 }
@@ -680,7 +683,9 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   char* ws = static_cast<char*>(workspace);
   void* G = ws + q.off_g;
   void* U = ws + q.off_u;
-  if (q.up_fast) {
+  if (q.gate_fused) {
+    launch_fast_gate(M, D, H, X, Wg, Wu, G, ws + q.off_xtail, s);
+  } else if (q.up_fast) {
     launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, G, ws + q.off_xtail, s);
     launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, U, ws + q.off_xtail, s);
   } else {
@@ -689,7 +694,7 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
     g.B = Wu;
     launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, U, s);
   }
-  launch_silu_mul((int)dt, M * H, G, U, G, s);
+  if (!q.gate_fused) launch_silu_mul((int)dt, M * H, G, U, G, s);
   if (q.down_fast) {
     launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, nullptr, nullptr, Y, nullptr, s);
   } else {

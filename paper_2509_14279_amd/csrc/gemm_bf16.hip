@@ -63,10 +63,12 @@ template <int BK> struct Geo {
 // EPI_STORE: C = acc.  EPI_BIAS: C = acc + bias.  EPI_F1: EPI_BIAS plus GELU and partial row statistics.
 // EPI_PARTIAL: fp32 partial sums of a split reduction.  EPI_RELU: C = max(acc + bias, 0).
 // EPI_MASK: C = aux where acc + bias > 0, else 0 (aux [J][I]: the upstream gradient of a ReLU).
-enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2, EPI_PARTIAL = 3, EPI_RELU = 4, EPI_MASK = 5 };
+// EPI_GATE: two P operands (gate and up weights), C = SiLU(Q P^T) * (Q P2^T): see the kernel's p_origin.
+enum { EPI_STORE = 0, EPI_F1 = 1, EPI_BIAS = 2, EPI_PARTIAL = 3, EPI_RELU = 4, EPI_MASK = 5, EPI_GATE = 6 };
 
 struct FastParams {
   const bf16_t* P; const bf16_t* Q;
+  const bf16_t* P2;      // EPI_GATE: the second P operand (same shape and pitch as P)
   const bf16_t* Qtail;   // RAG: the Q rows of the last (partial) row tile as a padded 256-row copy, or null if Q
                          //      itself has readable rows up to the end of that tile
   int64_t ldp, ldq;
@@ -273,7 +275,13 @@ void gemm_bf16_kernel(FastParams p) {
   const int64_t pstep = P_RM ? (int64_t)BK * p.ldp : BK;
   const int64_t qstep = Q_RM ? (int64_t)BK * p.ldq : BK;
   // first element this wave fetches of slice 0 of the tile at (i0, j0)
+  // EPI_GATE: the 256 rows of a P tile are 64 gate rows, the same 64 up rows, the next 64 gate rows and their up rows
+  // (rows of P and P2 from i0/2 on), one quarter per wave: a wave's accumulator blocks a = 0, 1 then hold the gate
+  // product and a = 2, 3 the up product of the same 64 output columns, register for register, and the gated
+  // activation needs no exchange between lanes.  The tile is 128 output columns wide.
   auto p_origin = [&](int i0) {
+    if (EPI == EPI_GATE)
+      return ((wave & 1) ? p.P2 : p.P) + (int64_t)((i0 >> 1) + (wave >> 1) * 64) * p.ldp + r_begin;
     return lp.wave_base(P_RM ? p.P + r_begin * p.ldp + i0 : p.P + (int64_t)i0 * p.ldp + r_begin, p.ldp, wave);
   };
   auto q_origin = [&](int j0) {
@@ -533,7 +541,37 @@ void gemm_bf16_kernel(FastParams p) {
         else *dst = v;
       }
     };
-    if (EPI == EPI_PARTIAL) {
+    if (EPI == EPI_GATE) {
+      // H = SiLU(gate) * up for this wave's 64 columns x 128 rows, one block row of 32 rows at a time through the
+      // staging area (units 0..15 of each 256-byte staging row), stored as 128-byte row segments
+      const int h0 = (i0 >> 1) + wi * 64;
+      const int g_m = le & 7, g_rq = le >> 3;      // read side: 16-byte chunk lane%8 of row it*8 + lane/8
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+#pragma unroll
+        for (int a = 0; a < 2; a++)
+#pragma unroll
+          for (int g = 0; g < 4; g++) {
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; e++) {
+              const float z = acc[a][b][g * 4 + e], u = acc[a + 2][b][g * 4 + e];
+              const float sg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504088896340736f * z));
+              v[e] = (bf16_t)(z * sg * u);
+            }
+            *(lds_bf16x4*)(wtile + woff[a][g]) = v;
+          }
+        char* cbase = reinterpret_cast<char*>(p.C + (int64_t)(j0 + wj * 128 + b * 32) * p.I + h0);
+#pragma unroll
+        for (int it = 0; it < 4; it++) {
+          const int row = it * 8 + g_rq;
+          const u32x4 v = *(const lds_u32x4*)(wtile + row * 256 + ((g_m ^ (row & 15)) << 4));
+          if (RAG && j0 + wj * 128 + b * 32 + row >= p.J) continue;   // a row past the end
+          *reinterpret_cast<u32x4*>(cbase + ((int64_t)row * p.I + g_m * 8) * 2) = v;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    } else if (EPI == EPI_PARTIAL) {
       // fp32 partial sums of this reduction part, straight from the registers (wave-uniform base + lane offset)
       float* out = p.Cpart + (int64_t)blockIdx.y * p.J * p.I;
       const uint32_t pvoff = (uint32_t)(e_l32 * p.I + e_half * 4) * 4u;
@@ -830,6 +868,31 @@ void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, b
   else if (bias != nullptr) FDL_XWT(EPI_BIAS);
   else FDL_XWT(EPI_STORE);
 #undef FDL_XWT
+}
+
+// Gated pair of products for the feed-forward block: Hout[m][h] = SiLU(sum_d X[m][d] Wg[h][d]) * (sum_d X[m][d] Wu[h][d]).
+// Shapes: H a multiple of 128, D of the pipeline round, M >= 128; ragged M as in launch_fast_xwt.
+bool fast_gate_supported(int64_t M, int64_t D, int64_t H) {
+  const int64_t tj = (M + kTile - 1) / kTile;
+  return M >= kMinRaggedRows && H > 0 && H % 128 == 0 && D > 0 && D % (stages_of(kF1BK) * kF1BK) == 0 && H <= (1 << 24) &&
+         M <= (1 << 24) && (H / 128) * tj <= (1 << 30);
+}
+void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, void* Hout,
+                      void* xtail, hipStream_t s) {
+  FastParams p = {};
+  p.P = (const bf16_t*)Wg; p.P2 = (const bf16_t*)Wu; p.Q = (const bf16_t*)X; p.ldp = D; p.ldq = D;
+  p.C = (bf16_t*)Hout;
+  p.I = (int)H; p.J = (int)M; p.tiles_i = (int)(H / 128); p.tiles_j = (int)((M + kTile - 1) / kTile);
+  p.nkt = (int)(D / kF1BK); p.split = 1;
+  constexpr int NS = stages_of(kF1BK);
+  if (M % kTile) {
+    p.Qtail = (const bf16_t*)xtail;
+    hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, D,
+                       (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail, kTile);
+    launch<false, false, EPI_GATE, kF1BK, NS, true>(p, s);
+  } else {
+    launch<false, false, EPI_GATE, kF1BK, NS, false>(p, s);
+  }
 }
 
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s) {

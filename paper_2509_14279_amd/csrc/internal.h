@@ -149,6 +149,10 @@ void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const voi
 // sibling operators on the forward product's kernel (see gemm_bf16.hip); shapes as fast_f1_supported
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
                      const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
+// gate and up products of the feed-forward block with the gated activation in the epilogue (see gemm_bf16.hip)
+bool fast_gate_supported(int64_t M, int64_t D, int64_t H);
+void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, void* Hout,
+                      void* xtail, hipStream_t s);
 // dZ must have readable rows up to the next multiple of 256
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s);
 int fast_b4_split(int64_t M, int64_t K, int64_t N);

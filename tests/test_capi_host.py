@@ -168,7 +168,8 @@ def test_sibling_entry_points_reject_bad_arguments_before_any_launch():
     assert api.fdl_rmsnorm_forward_raw("f32", 4, 4, P, P, -1.0, P, None) == api.FDL_ERR_EPS
     assert api.fdl_rmsnorm_forward_raw("f32", 0, 4, P, P, 1e-5, P, None) == api.FDL_OK
     # Llama feed-forward
-    assert api.fdl_llama_ffn_workspace_bytes("bf16", 1024, 512, 2048) >= 2 * 1024 * 2048 * 2
+    assert api.fdl_llama_ffn_workspace_bytes("bf16", 1024, 512, 2048) >= 1024 * 2048 * 2          # fused gate: one M x H buffer
+    assert api.fdl_llama_ffn_workspace_bytes("f32", 1024, 512, 2048) >= 2 * 1024 * 2048 * 4
     assert api.fdl_llama_ffn_workspace_bytes("bf16", 1024, 0, 2048) == 0
     assert api.fdl_llama_ffn_forward_raw("f32", 4, 4, 4, P, P, 0, P, P, P, big, None) == api.FDL_ERR_NULL
     assert api.fdl_llama_ffn_forward_raw("f32", 4, 4, 0, P, P, P, P, P, P, big, None) == api.FDL_ERR_SHAPE

@@ -193,8 +193,10 @@ def test_norms_constant_and_zero_rows():
 
 
 # ------------------------------------------------------------------ Llama feed-forward block
-# (dtype, M, D, H): fast path exact and with a ragged M; generic kernels (unaligned D or H); fp32
+# (dtype, M, D, H): fused gate/up kernel (H a multiple of 128) exact and with a ragged M, with the down projection on
+# the tuned kernel (D a multiple of 256) or the generic one (384); generic kernels throughout (unaligned D or H); fp32
 FFN_SHAPES = [("bf16", 512, 512, 1024), ("bf16", 300, 256, 768), ("bf16", 1024, 1024, 2816), ("bf16", 130, 100, 200),
+              ("bf16", 256, 128, 128), ("bf16", 640, 384, 384), ("bf16", 2049, 256, 1152),
               ("bf16", 64, 256, 264), ("f32", 130, 70, 200), ("f32", 33, 64, 128), ("f32", 1, 1, 1), ("bf16", 3, 5, 7)]
 
 
