@@ -132,6 +132,9 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
     q.b4_fast_rows = q.b4_fast ? fast_b4_rows(M) : 0;
   }
   q.b4_split = q.b4_fast ? fast_b4_split(q.b4_fast_rows, K, N) : 1;
+  q.pair_sa = q.pair_sb = 1;
+  q.pair = !q.pad && q.b3_fast && q.b4_fast && q.b4_fast_rows == M && fast_pair_plan(M, K, N, &q.pair_sa, &q.pair_sb);
+  if (q.pair) q.b4_split = q.pair_sb;
   // fp32 partial sums of dW: the parts of a split reduction, one more for the rows the fast kernel leaves to the
   // generic one; in padded mode the fast kernel always writes partials
   int b4_parts = q.b4_split + (q.b4_fast && q.b4_fast_rows < M ? 1 : 0);
@@ -144,6 +147,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.off_colpart = off; off += align256((size_t)q.b1_groups * 3 * N * cs);
   q.off_dwpart = off; off += align256(b4_parts > 1 ? (size_t)b4_parts * N * K * 4 : 0);
   q.off_wpad_b = off; off += align256(q.pad ? (size_t)Np * Kp * 2 : 0);
+  q.off_dxpart = off; off += align256(q.pair && q.pair_sa > 1 ? (size_t)q.pair_sa * M * K * 4 : 0);
   q.bwd_bytes = off;
   q.bytes = q.fwd_bytes > q.bwd_bytes ? q.fwd_bytes : q.bwd_bytes;
   *p = q;
@@ -372,7 +376,11 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   {
     // B3: dX[M,K] = dZ[M,N] W[N,K]
     PhaseTimer t(FDL_PHASE_B3, s);
-    if (p.pad) {
+    if (p.pair) {
+      // one launch for both contractions (B4 below only sums the partial sums of dW, where its reduction is split)
+      launch_fast_pair(M, K, N, p.pair_sa, p.pair_sb, dZ, W, X, dX, ws + p.off_dxpart, dW, ws + p.off_dwpart, s);
+      if (p.pair_sa > 1) launch_fast_b4_reduce(K, M, p.pair_sa, ws + p.off_dxpart, dX, s);
+    } else if (p.pad) {
       void* Wp = ws + p.off_wpad_b;
       launch_fast_pad_weights(K, N, W, nullptr, Wp, nullptr, s);
       launch_fast_b3_padded(M, K, N, dZ, Wp, dX, s);
@@ -386,7 +394,9 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   {
     // B4: dW[N,K] = dZ^T[N,M] X[M,K]
     PhaseTimer t(FDL_PHASE_B4, s);
-    if (p.pad && p.b4_fast) {
+    if (p.pair) {
+      if (p.pair_sb > 1) launch_fast_b4_reduce(K, N, p.pair_sb, ws + p.off_dwpart, dW, s);
+    } else if (p.pad && p.b4_fast) {
       // padded mode: the fast kernel writes fp32 partials of the first b4_fast_rows rows; the generic kernel adds one
       // for the remaining rows (there is always at least one when K is not a multiple of the tile)
       const int64_t Mf = p.b4_fast_rows;

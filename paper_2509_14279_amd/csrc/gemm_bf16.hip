@@ -225,14 +225,14 @@ __device__ __forceinline__ TileCoord tile_coord(int L, int tiles_i, int tiles_j)
 // and not stored, and are left out of the row statistics where the epilogue takes them.
 // A reduction length that is not a whole number of pipeline rounds is the host's business as well: it rounds the
 // length up and makes one operand zero over the surplus (the other only has to be readable and finite there).
+// The body of the kernel: the persistent tile loop of workgroup `bid` of `nblk` on reduction part `part`.  It is a
+// function of its own so that one launch can carry two contractions side by side (see gemm_bf16_pair_kernel).
 template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG, bool CRAG = false>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-void gemm_bf16_kernel(FastParams p) {
+__device__ __forceinline__ void gemm_tile_loop(const FastParams& p, char* smem, const int bid, const int nblk, const int part) {
   static_assert(!CRAG || RAG, "ragged columns come with the ragged-row checks");
   typedef Geo<BK> G;
   static_assert(NS * G::kStageBytes == kLdsStages, "stages must fill 128 KB");
   static_assert((NS == 2 || NS == 4) && (G::kSub & 1) == 0, "2 or 4 stages, even number of sub-slices");
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
   lds_char* lds = (lds_char*)smem;
   const uint32_t lds0 = (uint32_t)(uintptr_t)lds;
   const int lane = threadIdx.x & 63;
@@ -249,14 +249,14 @@ void gemm_bf16_kernel(FastParams p) {
   if (p.xcds > 1) {
     const int X = p.xcds;
     const int per_xcd = ntiles / X;
-    const int xcd = (int)blockIdx.x % X, slot = (int)blockIdx.x / X;
+    const int xcd = bid % X, slot = bid / X;
     L = xcd * per_xcd + slot;
-    Lstride = (int)gridDim.x / X;
+    Lstride = nblk / X;
     Lend = (xcd + 1) * per_xcd;
   } else {
-    L = blockIdx.x; Lstride = gridDim.x; Lend = ntiles;
+    L = bid; Lstride = nblk; Lend = ntiles;
   }
-  const int64_t r_begin = (int64_t)blockIdx.y * p.nkt * BK;
+  const int64_t r_begin = (int64_t)part * p.nkt * BK;
 
   // Per-lane offsets of the direct loads and of the fragment reads.  They are recomputed at the top of every tile
   // (from a copy of the lane id the compiler cannot see through) rather than kept across the epilogue, where the
@@ -573,7 +573,7 @@ void gemm_bf16_kernel(FastParams p) {
       }
     } else if (EPI == EPI_PARTIAL) {
       // fp32 partial sums of this reduction part, straight from the registers (wave-uniform base + lane offset)
-      float* out = p.Cpart + (int64_t)blockIdx.y * p.J * p.I;
+      float* out = p.Cpart + (int64_t)part * p.J * p.I;
       const uint32_t pvoff = (uint32_t)(e_l32 * p.I + e_half * 4) * 4u;
 #pragma unroll
       for (int b = 0; b < 4; b++) {
@@ -661,6 +661,30 @@ void gemm_bf16_kernel(FastParams p) {
     L = Ln; tc = tn;
   }
   wait_dma<0>();   // the re-fetches issued during the last tile must land before the workgroup may retire
+}
+
+template <bool P_RM, bool Q_RM, int EPI, int BK, int NS, bool RAG, bool CRAG = false>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_bf16_kernel(FastParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  gemm_tile_loop<P_RM, Q_RM, EPI, BK, NS, RAG, CRAG>(p, smem, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y);
+}
+
+// Two contractions in one launch: the dX product on the first na * (parts of its reduction) workgroups and the dW
+// product on the rest (nb workgroups per part of its reduction); a split reduction writes fp32 partial sums.  For
+// outputs so small that neither contraction has a tile for every compute unit - a dX with few column tiles, a small
+// dW - the two together still fill the chip, where two launches in a row would each leave part of it idle.
+template <int BK, int NS, int EPIA, int EPIB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+void gemm_bf16_pair_kernel(FastParams pa, FastParams pb, int na, int nb) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int id = (int)blockIdx.x, a_all = na * pa.split;
+  if (id < a_all) {
+    gemm_tile_loop<true, false, EPIA, BK, NS, false>(pa, smem, id % na, na, id / na);
+  } else {
+    const int t = id - a_all;
+    gemm_tile_loop<true, true, EPIB, BK, NS, false>(pb, smem, t % nb, nb, t / nb);
+  }
 }
 
 // Sum split-reduction partials [split][n] fp32 -> bf16.
@@ -959,6 +983,68 @@ void launch_fast_b4_reduce(int64_t K, int64_t N, int parts, const void* dwpart, 
   const int64_t n = N * K;
   hipLaunchKernelGGL(reduce_split_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s,
                      (const float*)dwpart, parts, n, (bf16_t*)dW);
+}
+
+// dX and dW in one launch (see gemm_bf16_pair_kernel): for shapes where every dimension is a whole number of tiles and
+// the two outputs together have at most one tile per compute unit of the plan's part (kPlanCUs: the split is part of
+// the workspace plan and must not depend on the device).  The reductions (over N for dX, over M for dW) are split into
+// sa and sb parts - whole pipeline rounds of at least 512 - so that the workgroups fill the chip and the longer of the
+// two kinds of workgroup is as short as possible.  Returns false if the shape does not qualify.
+bool fast_pair_plan(int64_t M, int64_t K, int64_t N, int* sa_out, int* sb_out) {
+  if (static_cast<int>(kB3BK) != static_cast<int>(kB4BK)) return false;
+  if (M % kTile || !dims_ok(K, M, N, kB3BK) || !dims_ok(K, N, M, kB4BK)) return false;
+  const int64_t ta = (K / kTile) * (M / kTile), tb = (K / kTile) * (N / kTile);
+  if (ta + tb > kPlanCUs) return false;
+  const int64_t unit = (int64_t)kB3BK * stages_of(kB3BK);
+  int best_sa = 0, best_sb = 0;
+  int64_t best_len = 0, best_wgs = 0;
+  for (int sa = 1; sa <= 16; sa *= 2) {
+    if (N % (sa * unit) || (sa > 1 && N / sa < 512)) break;
+    for (int sb = 1; sb <= 16; sb *= 2) {
+      if (M % (sb * unit) || (sb > 1 && M / sb < 512)) break;
+      const int64_t wgs = ta * sa + tb * sb;
+      if (wgs > kPlanCUs) break;
+      const int64_t len = N / sa > M / sb ? N / sa : M / sb;     // reduction length of the longest workgroup
+      if (best_sa == 0 || len < best_len || (len == best_len && wgs < best_wgs)) {
+        best_sa = sa; best_sb = sb; best_len = len; best_wgs = wgs;
+      }
+    }
+  }
+  if (best_sa == 0) return false;
+  *sa_out = best_sa; *sb_out = best_sb;
+  return true;
+}
+
+// dxpart: sa [M][K] fp32 partial sums (sa > 1), dwpart: sb [N][K] (sb > 1); an unsplit product goes to dX / dW directly.
+// The caller sums the partials (launch_fast_b4_reduce works for either).
+void launch_fast_pair(int64_t M, int64_t K, int64_t N, int sa, int sb, const void* dZ, const void* W, const void* X,
+                      void* dX, void* dxpart, void* dW, void* dwpart, hipStream_t s) {
+  FastParams pa = {}, pb = {};
+  pa.P = (const bf16_t*)W; pa.Q = (const bf16_t*)dZ; pa.ldp = K; pa.ldq = N; pa.C = (bf16_t*)dX; pa.Cpart = (float*)dxpart;
+  pa.I = (int)K; pa.J = (int)M; pa.tiles_i = (int)(K / kTile); pa.tiles_j = (int)(M / kTile);
+  pa.nkt = (int)(N / kB3BK / sa); pa.split = sa;
+  pb.P = (const bf16_t*)X; pb.Q = (const bf16_t*)dZ; pb.ldp = K; pb.ldq = N; pb.C = (bf16_t*)dW; pb.Cpart = (float*)dwpart;
+  pb.I = (int)K; pb.J = (int)N; pb.tiles_i = (int)(K / kTile); pb.tiles_j = (int)(N / kTile);
+  pb.nkt = (int)(M / kB4BK / sb); pb.split = sb;
+  DeviceInfo di;
+  if (!device_info(&di)) return;
+  const int na = pa.tiles_i * pa.tiles_j, nb = pb.tiles_i * pb.tiles_j;     // one tile per workgroup
+  const bool die_aware = di.xcds > 1 && na % di.xcds == 0 && nb % di.xcds == 0;
+  pa.xcds = die_aware ? di.xcds : 1; pb.xcds = pa.xcds;
+  const dim3 grid((unsigned)(na * sa + nb * sb));
+  constexpr int NS = stages_of(kB3BK);
+#define FDL_PAIR(EA, EB)                                                                                   \
+  do {                                                                                                     \
+    static OnceFlags configured;                                                                           \
+    auto kern = gemm_bf16_pair_kernel<kB3BK, NS, EA, EB>;                                                  \
+    if (!ensure_dynamic_lds(reinterpret_cast<const void*>(kern), kLdsBytes, &configured)) return;          \
+    hipLaunchKernelGGL(kern, grid, dim3(256), kLdsBytes, s, pa, pb, na, nb);                               \
+  } while (0)
+  if (sa > 1 && sb > 1) FDL_PAIR(EPI_PARTIAL, EPI_PARTIAL);
+  else if (sa > 1) FDL_PAIR(EPI_PARTIAL, EPI_STORE);
+  else if (sb > 1) FDL_PAIR(EPI_STORE, EPI_PARTIAL);
+  else FDL_PAIR(EPI_STORE, EPI_STORE);
+#undef FDL_PAIR
 }
 
 }  // namespace fdl

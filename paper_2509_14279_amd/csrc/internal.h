@@ -39,6 +39,9 @@ struct Plan {
   int b3_wb, b4_wb;
   int b4_split;           // split of the reduction over M in B4 (fast kernel)
   int64_t b4_fast_rows;   // rows of the reduction the fast kernel covers (the rest goes through the generic kernel)
+  int pair;               // 1: dX and dW share one launch, their reductions split into pair_sa and pair_sb parts
+  int pair_sa, pair_sb;
+  size_t off_dxpart;      // float [pair_sa][M][K] (pair_sa > 1)
   int pad;                // 1: padded mode of the fast contractions (N, K multiples of 8, not both of 256)
   int64_t ldz;            // pitch of the dZ buffer in elements (N, or N rounded up to 256 in padded mode)
   size_t off_wpad_f, off_bpad_f;   // forward: zero-padded copies of W [Np][Kp] and b [Np]
@@ -159,5 +162,9 @@ int fast_b4_split(int64_t M, int64_t K, int64_t N);
 void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, const void* X, void* dW,
                     void* dwpart, hipStream_t s);
 void launch_fast_b4_reduce(int64_t K, int64_t N, int parts, const void* dwpart, void* dW, hipStream_t s);
+// dX and dW in one launch where together they have at most a tile per compute unit; sa, sb: parts of the two reductions
+bool fast_pair_plan(int64_t M, int64_t K, int64_t N, int* sa, int* sb);
+void launch_fast_pair(int64_t M, int64_t K, int64_t N, int sa, int sb, const void* dZ, const void* W, const void* X,
+                      void* dX, void* dxpart, void* dW, void* dwpart, hipStream_t s);
 
 }  // namespace fdl
