@@ -31,6 +31,15 @@ bool shape_ok(int64_t M, int64_t K, int64_t N) {
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 
+// Block tile of the generic kernel (as 16 x 16 blocks per wave tile side): 128 x 128 where that still gives every
+// compute unit a tile, else 64 x 64.  fp32 storage always takes the small tile: its fp64 accumulators leave room for
+// one workgroup per compute unit only at the large one, and with four the latencies of its register-staged loads are
+// covered (measured: twice as fast on the forward contraction of the ragged fp32 configuration).
+int pick_generic_wb(int dt, int64_t I, int64_t J) {
+  if (dt == kF32) return 2;
+  return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2;
+}
+
 thread_local bool t_failure_noted = false;
 
 }  // namespace
@@ -93,7 +102,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   const int64_t Np = q.pad ? fast_pad_dim(N) : N, Kp = q.pad ? fast_pad_dim(K) : K;
   q.ldz = Np;
   const int64_t Mp = M > 0 ? M : 1;
-  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  auto pick_wb = [dt](int64_t I, int64_t J) { return pick_generic_wb(dt, I, J); };
 
   // ---- forward
   q.f1_fast = q.pad || (dt == kBF16 && fast_f1_supported(M, K, N));
@@ -495,7 +504,7 @@ bool make_relu_plan(int dt, int64_t M, int64_t K, int64_t N, ReluPlan* q) {
   if (!shape_ok(M, K, N)) return false;
   const size_t ts = dt == kF32 ? 4 : 2, cs = dt == kF32 ? 8 : 4;
   const int64_t Mp = M > 0 ? M : 1;
-  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  auto pick_wb = [dt](int64_t I, int64_t J) { return pick_generic_wb(dt, I, J); };
   // the tuned kernels where the shape fits their tiles and pipeline rounds as it is; the generic kernel otherwise
   q->f1_fast = dt == kBF16 && fast_f1_supported(M, K, N);
   q->b3_fast = dt == kBF16 && fast_b3_supported(M, K, N);
@@ -655,7 +664,7 @@ bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   if (M * H > kMaxElems || M * D > kMaxElems || H * D > kMaxElems) return false;
   const size_t ts = dt == kF32 ? 4 : 2;
   const int64_t Mp = M > 0 ? M : 1;
-  auto pick_wb = [](int64_t I, int64_t J) { return (((I + 127) / 128) * ((J + 127) / 128) >= 256) ? 4 : 2; };
+  auto pick_wb = [dt](int64_t I, int64_t J) { return pick_generic_wb(dt, I, J); };
   q->gate_fused = dt == kBF16 && fast_gate_supported(M, D, H);
   q->up_fast = dt == kBF16 && fast_f1_supported(M, D, H);      // [M,D] x [H,D]^T
   q->down_fast = dt == kBF16 && fast_f1_supported(M, H, D);    // [M,H] x [D,H]^T
