@@ -8,8 +8,8 @@ dominant kernel (timed live with HIP events on the launch stream), per-phase tim
 and the fp64 oracle timed on the host cores on a bounded sample of the same workload.
 
 Timing: W untimed warm-up steps, then K steps under the wall clock with device synchronisation on both sides and
-nothing but the two calls inside the loop (`value`); per-step and per-phase times come from a second, separate pass
-of K steps with HIP events (`ms_per_step_min`, `phases`).  The machine's own ceilings (a register-resident MFMA
+nothing but the two calls inside the loop (`value`); the per-step minimum comes from a second pass with one event
+between steps (`ms_per_step_min`) and the per-phase times from a third with HIP events around every phase (`phases`).  The machine's own ceilings (a register-resident MFMA
 loop, streaming kernels) are measured in the same process after the timed region and reported next to the
 published peaks (`measured_peak`, `frac_of_measured`, `frac_measured`).
 
@@ -62,6 +62,12 @@ class HipEvents:
 
     def destroy(self, e: int):
         self.hip.hipEventDestroy(e)
+
+    def clock_ghz(self, device: int = 0) -> float:
+        """Maximum engine clock of the device (hipDeviceAttributeClockRate, reported in kHz), 0 if unavailable."""
+        v = ctypes.c_int(0)
+        rc = self.hip.hipDeviceGetAttribute(ctypes.byref(v), 5, device)
+        return v.value / 1e6 if rc == 0 else 0.0
 
 
 class Ceilings:
@@ -117,6 +123,29 @@ class Ceilings:
         torch.cuda.synchronize()
         return out.cpu().view(-1, 2)[:, 0].double().median().item() / (iters * 8)
 
+    def lds_lane_groups(self, kind=16, iters=2000):
+        """Which lanes of an LDS read instruction are served together?  Every lane reads one common address (a broadcast,
+        conflict-free) except lanes i and j, which read two other addresses on the same banks; the read takes longer
+        exactly when i and j are served in the same cycle.  Returns the groups as sorted lane lists."""
+        import numpy as np
+        base = self.lds_table(np.full((8, 64), 128), kind, iters)
+        slow = np.zeros((64, 64), dtype=bool)
+        times = np.zeros((64, 64))
+        for i in range(64):
+            for j in range(i + 1, 64):
+                off = np.full(64, 128); off[i] = 0; off[j] = 1024
+                times[i, j] = times[j, i] = self.lds_table(np.tile(off, (8, 1)), kind, iters)
+        thr = (times.max() + base) / 2
+        slow = times > thr
+        groups, seen = [], set()
+        for i in range(64):
+            if i in seen:
+                continue
+            g = sorted({i} | {j for j in range(64) if slow[i, j]})
+            seen |= set(g)
+            groups.append(g)
+        return groups, base, float(times[times > 0].min()), float(times.max())
+
     def streams(self, gib=1.0, grids=(256, 512, 1024, 4096), reps=5):
         """Best GB/s over a few launch shapes of read-only, write-only, copy and two-reads-one-write streaming."""
         torch = self.torch
@@ -144,7 +173,7 @@ class Ceilings:
         cycle and CU, and the shader clock during the probe."""
         torch = self.torch
         rows = []
-        for pat in range(7):
+        for pat in range(10):
             out = torch.zeros(2 * self.cus, dtype=torch.int64, device="cuda")
             assert self.L.fdlc_lds_probe(pat, self.cus, iters, out.data_ptr(), self.stream) == 0
             torch.cuda.synchronize()
@@ -157,13 +186,13 @@ class Ceilings:
         return rows
 
 
-def run_ceilings():
+def run_ceilings(lane_groups: bool = True):
     """Text table of the measured ceilings (the figures quoted in the design notes come from this mode)."""
     import torch
     ev = HipEvents()
     c = Ceilings(ev)
     prop = torch.cuda.get_device_properties(0)
-    clk = getattr(prop, "clock_rate", 0) / 1e6
+    clk = ev.clock_ghz()
     print(f"device: {prop.name}, {prop.multi_processor_count} CUs, max engine clock {clk:.2f} GHz")
     print(f"  MFMA peak from unit counts: {prop.multi_processor_count} CUs x 4 SIMDs x 1024 flop/clk (bf16 32x32x16: 32768 flop in 32 cycles)"
           f" x {clk:.2f} GHz = {prop.multi_processor_count * 4 * 1024 * clk / 1e3:.0f} TFLOP/s; published 2500 TFLOP/s")
@@ -175,6 +204,24 @@ def run_ceilings():
     print("LDS read probes (4 waves per CU, 8 independent reads per loop round, shader-clock timed):")
     for r in c.lds_probes():
         print(f"  {r['pattern']:62s} {r['cycles_per_read_per_wave']:7.2f} cycles/read/wave  {r['bytes_per_cycle_per_cu']:7.1f} B/clk/CU  at {r['clock_GHz']:.2f} GHz")
+    if not lane_groups:
+        return
+    print("LDS lane groups (pairwise conflict probe: all lanes broadcast-read one address, two lanes read others on the same banks):")
+
+    def ranges(g):
+        out, a, b = [], g[0], g[0]
+        for x in g[1:]:
+            if x == b + 1:
+                b = x
+            else:
+                out.append((a, b)); a = b = x
+        out.append((a, b))
+        return " ".join(f"{a}-{b}" if a != b else f"{a}" for a, b in out)
+    for kind, name in ((16, "ds_read_b128"), (8, "ds_read_b64"), (4, "ds_read_b32")):
+        groups, base, lo, hi = c.lds_lane_groups(kind)
+        print(f"  {name}: {len(groups)} group(s) of {len(groups[0])} lanes; cycles/read/wave {base:.2f} without, {hi:.2f} with a conflicting pair")
+        for g in groups:
+            print(f"      lanes {ranges(g)}")
     out = {"mfma_bf16_tflops": round(c.mfma_bf16(waves=4), 1), **{f"stream_{k}_gbs": round(v, 1) for k, v in st.items()}}
     print("CEILINGS_JSON: " + json.dumps(out))
 
@@ -463,6 +510,8 @@ def main():
                     help="print the measured ceilings (MFMA loop, streaming, LDS access-pattern probes) as a text table")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy a few times (reference point for HBM byte counters)")
+    ap.add_argument("--no-lane-groups", action="store_true",
+                    help="with --ceilings: skip the pairwise LDS lane-group probe (some six thousand tiny launches)")
     ap.add_argument("--siblings", action="store_true",
                     help="time the forward-only entry point and the sibling operators (one JSON line each)")
     ap.add_argument("--sweep", action="store_true",
@@ -481,7 +530,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
     if args.ceilings:
-        run_ceilings()
+        run_ceilings(lane_groups=not args.no_lane_groups)
         return
     if args.sweep:
         run_sweep(min(args.steps, 20), min(args.warmup, 5))
@@ -529,20 +578,26 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    # ---- second pass (not part of `value`): per-step and per-phase times with HIP events on the launch stream
-    ev = HipEvents()
-    nph = len(api.FDL_PHASES)
-    sets = [[ev.create() for _ in range(2 * nph)] for _ in range(args.steps)]
+    # ---- second pass (not part of `value`): one event between steps, for the per-step minimum and mean
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     marks[0].record()
     for k in range(args.steps):
-        api.fdl_set_phase_events(sets[k])
         step()
         marks[k + 1].record()
     torch.cuda.synchronize()
-    api.fdl_set_phase_events(None)
     step_ms = [marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)]
+
+    # ---- third pass: per-phase times with HIP events recorded by the library on the launch stream
+    ev = HipEvents()
+    nph = len(api.FDL_PHASES)
+    sets = [[ev.create() for _ in range(2 * nph)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    for k in range(args.steps):
+        api.fdl_set_phase_events(sets[k])
+        step()
+    torch.cuda.synchronize()
+    api.fdl_set_phase_events(None)
     phase_ms = {}
     for p, name in enumerate(api.FDL_PHASES):
         phase_ms[name] = sum(ev.elapsed_ms(s[2 * p], s[2 * p + 1]) for s in sets) / args.steps
@@ -601,13 +656,13 @@ def main():
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "us_per_step": round(ms_per_step * 1e3, 1),
-        "ms_per_step_min": round(min(step_ms), 4), "ms_per_step_mean_second_pass": round(sum(step_ms) / len(step_ms), 4),
+        "ms_per_step_min": round(min(step_ms), 4), "ms_per_step_mean_event_pass": round(sum(step_ms) / len(step_ms), 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f64",
         "data": "synthetic",
         "config": {"workload": cfg.name, "M": M, "K": K, "N": N, "storage": cfg.dtype, "seed": cfg.seed,
                    "timing": "wall clock around K steps (two calls per step, nothing else in the loop), inputs resident in "
-                             "HBM, caches warm; min and per-phase times from a second pass with HIP events"},
+                             "HBM, caches warm; per-step minimum and per-phase times from separate passes with HIP events"},
         "roofline": roofline,
         "phases": phases,
     }

@@ -612,13 +612,16 @@ template <class T> void f2_impl(int64_t M, int64_t N, const void* Z, const float
   constexpr int VMAX = 16 / (int)sizeof(T);
   const int V = vec_width<T>(Z, Y, nullptr, N);
   const int strips = (int)((N + 256 * (int64_t)V - 1) / (256 * (int64_t)V));
-  const int rows_per_wg = 16;
+  // 16 rows per workgroup keep gamma and beta in registers across rows; fewer where the matrix is so small that the
+  // chip would otherwise see only a handful of workgroups
+  int64_t rows_per_wg = M * strips / 2048;
+  rows_per_wg = rows_per_wg < 1 ? 1 : (rows_per_wg > 16 ? 16 : rows_per_wg);
   const int64_t blocks = (int64_t)strips * ((M + rows_per_wg - 1) / rows_per_wg);
   if (V == VMAX)
-    hipLaunchKernelGGL((f2_kernel<T, VMAX>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_wg, strips,
+    hipLaunchKernelGGL((f2_kernel<T, VMAX>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, (int)rows_per_wg, strips,
                        (const T*)Z, mean, rstd, gamma, beta, (T*)Y);
   else
-    hipLaunchKernelGGL((f2_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, rows_per_wg, strips,
+    hipLaunchKernelGGL((f2_kernel<T, 1>), dim3((unsigned)blocks), dim3(256), 0, s, M, N, (int)rows_per_wg, strips,
                        (const T*)Z, mean, rstd, gamma, beta, (T*)Y);
 }
 

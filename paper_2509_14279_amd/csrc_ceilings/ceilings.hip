@@ -129,23 +129,32 @@ __global__ __launch_bounds__(kStreamThreads) void stream_mix21_kernel(u32x4* __r
 // ---------------------------------------------------------------------------------------------- LDS probes
 // Lane -> byte offset inside a 64 KB LDS tile for each pattern (the formulas of the GEMM kernel's fragment reads
 // are restated here on purpose: this file shares no code with the library).
+// (7-9: the swizzles the GEMM kernel used before, laid out for 32 banks - kept as the reference for what a two-way
+// conflict costs and for what the bank-conflict counter reads on it.)
 enum { LDS_B128_LINEAR = 0, LDS_B128_GEMM_BK64 = 1, LDS_B128_GEMM_BK32 = 2, LDS_TR16_GEMM = 3, LDS_B128_SAME_BANK = 4,
-       LDS_B64_LINEAR = 5, LDS_B32_LINEAR = 6, LDS_PATTERNS = 7 };
+       LDS_B64_LINEAR = 5, LDS_B32_LINEAR = 6, LDS_B128_OLD_BK64 = 7, LDS_B128_OLD_BK32 = 8, LDS_TR16_OLD = 9,
+       LDS_PATTERNS = 10 };
 
 template <int PAT> __device__ __forceinline__ uint32_t lds_offset(int lane, int step) {
   if (PAT == LDS_B128_LINEAR) return (uint32_t)(lane * 16 + step * 1024);
-  if (PAT == LDS_B128_GEMM_BK64) {   // rows of 128 B; 16-byte chunk c of row r in slot c ^ (r & 7); sub-slice kk = step & 3
-    const int row = (lane & 31) + 32 * (step >> 2), t0 = (lane >> 5) ^ (lane & 7), kk = step & 3;
-    return (uint32_t)(row * 128 + ((((kk << 1) ^ t0) & 7) << 4));
+  if (PAT == LDS_B128_GEMM_BK64 || PAT == LDS_B128_OLD_BK64) {
+    // rows of 128 B; 16-byte chunk c of row r in slot c ^ ((r >> 1) & 7) (before: c ^ (r & 7)); sub-slice kk = step & 3
+    const int row = (lane & 31) + 32 * (step >> 2), kk = step & 3, c = (kk << 1) | (lane >> 5);
+    const int sw = PAT == LDS_B128_GEMM_BK64 ? (row >> 1) & 7 : row & 7;
+    return (uint32_t)(row * 128 + (((c ^ sw) & 7) << 4));
   }
-  if (PAT == LDS_B128_GEMM_BK32) {   // rows of 64 B; chunk c of row r in slot c ^ ((r >> 1) & 3)
-    const int row = (lane & 31) + 32 * (step >> 1), sw = (lane >> 1) & 3, kk = step & 1;
-    return (uint32_t)(row * 64 + ((((kk << 1) | (lane >> 5)) ^ sw) << 4));
+  if (PAT == LDS_B128_GEMM_BK32 || PAT == LDS_B128_OLD_BK32) {
+    // rows of 64 B; chunk c of row r in slot c ^ ((r >> 2) & 3) (before: c ^ ((r >> 1) & 3))
+    const int row = (lane & 31) + 32 * (step >> 1), kk = step & 1, c = (kk << 1) | (lane >> 5);
+    const int sw = PAT == LDS_B128_GEMM_BK32 ? (row >> 2) & 3 : (row >> 1) & 3;
+    return (uint32_t)(row * 64 + (((c ^ sw) & 3) << 4));
   }
-  if (PAT == LDS_TR16_GEMM) {        // r-major tile [r][32 chunks of 16 B], chunk c of r-row w in slot c ^ ((w & 3) << 1)
+  if (PAT == LDS_TR16_GEMM || PAT == LDS_TR16_OLD) {
+    // r-major tile [r][32 chunks of 16 B], chunk c of r-row w in slot c ^ ((w & 3) << 2) (before: << 1)
     const int G = lane >> 4, p = lane & 15, r = 8 * (G >> 1) + (p >> 2);
     const int c = (step & 3) * 4 + 2 * (G & 1) + ((p & 3) >> 1);
-    return (uint32_t)((r + 16 * (step >> 2)) * 512 + ((c ^ ((p >> 2) << 1)) * 16) + (p & 1) * 8);
+    const int sw = (p >> 2) << (PAT == LDS_TR16_GEMM ? 2 : 1);
+    return (uint32_t)((r + 16 * (step >> 2)) * 512 + ((c ^ sw) * 16) + (p & 1) * 8);
   }
   if (PAT == LDS_B128_SAME_BANK) return (uint32_t)(lane * 512 + step * 16);   // every lane on the same banks
   if (PAT == LDS_B64_LINEAR) return (uint32_t)(lane * 8 + step * 512);
@@ -169,11 +178,11 @@ __global__ __launch_bounds__(256) void lds_probe_kernel(int iters, int64_t* out)
   uint32_t keep = 0;
   const int64_t c0 = (int64_t)clock64(), t0 = (int64_t)wall_clock64();
   for (int it = 0; it < iters; it++) {
-    if (PAT == LDS_TR16_GEMM || PAT == LDS_B64_LINEAR) {
+    if (PAT == LDS_TR16_GEMM || PAT == LDS_TR16_OLD || PAT == LDS_B64_LINEAR) {
       u32x2 v[8];
 #pragma unroll
       for (int s = 0; s < 8; s++) {
-        if (PAT == LDS_TR16_GEMM) asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v[s]) : "v"(off[s]));
+        if (PAT != LDS_B64_LINEAR) asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v[s]) : "v"(off[s]));
         else asm volatile("ds_read_b64 %0, %1" : "=v"(v[s]) : "v"(off[s]));
       }
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -299,7 +308,10 @@ FDLC_API int fdlc_lds_probe(int pattern, int grid, int iters, int64_t* out, void
     case 3: hipLaunchKernelGGL(lds_probe_kernel<3>, dim3(grid), dim3(256), 0, s, iters, out); break;
     case 4: hipLaunchKernelGGL(lds_probe_kernel<4>, dim3(grid), dim3(256), 0, s, iters, out); break;
     case 5: hipLaunchKernelGGL(lds_probe_kernel<5>, dim3(grid), dim3(256), 0, s, iters, out); break;
-    default: hipLaunchKernelGGL(lds_probe_kernel<6>, dim3(grid), dim3(256), 0, s, iters, out); break;
+    case 6: hipLaunchKernelGGL(lds_probe_kernel<6>, dim3(grid), dim3(256), 0, s, iters, out); break;
+    case 7: hipLaunchKernelGGL(lds_probe_kernel<7>, dim3(grid), dim3(256), 0, s, iters, out); break;
+    case 8: hipLaunchKernelGGL(lds_probe_kernel<8>, dim3(grid), dim3(256), 0, s, iters, out); break;
+    default: hipLaunchKernelGGL(lds_probe_kernel<9>, dim3(grid), dim3(256), 0, s, iters, out); break;
   }
   return hipGetLastError() == hipSuccess ? 0 : 2;
 }
@@ -318,7 +330,7 @@ FDLC_API int fdlc_lds_probe_table(const uint32_t* offsets, int kind, int grid, i
 }
 FDLC_API int fdlc_lds_probe_bytes(int pattern) {
   switch (pattern) {
-    case 3: case 5: return 64 * 8;
+    case 3: case 5: case 9: return 64 * 8;
     case 6: return 64 * 4;
     default: return 64 * 16;
   }
@@ -327,6 +339,7 @@ FDLC_API const char* fdlc_lds_probe_name(int pattern) {
   static const char* names[] = {"ds_read_b128 linear (lane*16)", "ds_read_b128 GEMM fragment, 128-byte rows (BK=64 swizzle)",
                                 "ds_read_b128 GEMM fragment, 64-byte rows (BK=32 swizzle)", "ds_read_b64_tr_b16 GEMM fragment (r-major tile)",
                                 "ds_read_b128 all lanes on the same banks (stride 512)", "ds_read_b64 linear (lane*8)",
-                                "ds_read_b32 linear (lane*4)"};
+                                "ds_read_b32 linear (lane*4)", "ds_read_b128 128-byte rows, former 32-bank swizzle",
+                                "ds_read_b128 64-byte rows, former 32-bank swizzle", "ds_read_b64_tr_b16 r-major tile, former 32-bank swizzle"};
   return (pattern >= 0 && pattern < LDS_PATTERNS) ? names[pattern] : "?";
 }
