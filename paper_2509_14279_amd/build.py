@@ -26,6 +26,8 @@ FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # only the extern "C" entry points marked in include/fdl.h are exported
     "-fvisibility=hidden",
+    # the normal-distribution table of the row kernels is evaluated by the compiler (common.hip.h)
+    "-fconstexpr-steps=200000000",
     # keep the compiler from forming packed-fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument", "-Wno-inline-asm",

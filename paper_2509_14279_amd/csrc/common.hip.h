@@ -84,33 +84,77 @@ template <> struct Gauss<float> {
 template <class C> __device__ __forceinline__ C gelu(C z) { return Gauss<C>::gelu_of(z, Gauss<C>::cdf(z)); }
 
 // ---------------------------------------------------------------------------------------------
+// Compile-time evaluation of the normal distribution in double precision (for the table below: its entries are
+// constants, so the compiler computes them once instead of every workgroup at every launch).
+namespace ctmath {
+constexpr double kLn2 = 0.69314718055994530941723212145818;
+constexpr double kInvSqrtPi = 0.56418958354775628694807945156077;
+// exp(-t), t >= 0: -t = -k ln 2 - r with |r| <= ln2 / 2, a 24-term series for exp(-r), then k halvings
+constexpr double exp_neg(double t) {
+  if (t > 700.0) return 0.0;
+  const long k = (long)(t / kLn2 + 0.5);
+  const double r = t - (double)k * kLn2;
+  double term = 1.0, sum = 1.0;
+  for (int n = 1; n <= 24; n++) { term *= -r / (double)n; sum += term; }
+  for (long i = 0; i < k; i++) sum *= 0.5;
+  return sum;
+}
+// erf(x), x >= 0: the Maclaurin series below 2.5 (its largest term is about e^6, so cancellation costs 3 of 16 digits),
+// 1 - erfc(x) from the continued fraction erfc(x) = exp(-x^2) / sqrt(pi) / (x + (1/2)/(x + 1/(x + (3/2)/(x + ...)))) above
+constexpr double erf_pos(double x) {
+  if (x < 2.5) {
+    const double x2 = x * x;
+    double term = x, sum = x;
+    for (int n = 1; n <= 90; n++) {
+      term *= -x2 / (double)n;
+      sum += term / (double)(2 * n + 1);
+    }
+    return 2.0 * kInvSqrtPi * sum;
+  }
+  double f = x;
+  for (int n = 120; n >= 1; n--) f = x + 0.5 * (double)n / f;
+  return 1.0 - exp_neg(x * x) * kInvSqrtPi / f;
+}
+}  // namespace ctmath
+
+// ---------------------------------------------------------------------------------------------
 // Exact Phi for bf16 arguments, from a table in LDS.  A bf16 number has 8 significant bits, so the magnitudes in
 // [2^-14, 16) are only 18 binades x 128 = 2304 values; for each of them the table holds
 //   H = Phi(|z|) - 1/2      and (kPair) Q = |z| phi(|z|),
 // both odd in z, as fp32 roundings of an fp64 evaluation.  Smaller magnitudes use the first entry (H, Q < 2.5e-5)
 // and larger ones the last (H = 1/2, Q = 0 to fp32).  A lookup is: clamp the magnitude bits, one LDS read, copy
 // the sign of z onto the entries - five integer instructions instead of the eleven of the polynomial, and
-// GELU(z) = z (1/2 + sign(z) H) carries no approximation error beyond fp32 rounding.  Every workgroup builds
-// its own copy (a few fp64 evaluations per thread), so there is no global state to initialise.
+// GELU(z) = z (1/2 + sign(z) H) carries no approximation error beyond fp32 rounding.  The entries are compile-time
+// constants in device memory; every workgroup copies them into its LDS (coalesced, a few KB from the L2).
+constexpr uint32_t kGaussLo = 0x3880u;          // bf16 bits of 2^-14
+constexpr uint32_t kGaussHi = 0x417fu;          // bf16 bits of the largest bf16 number below 16
+constexpr int kGaussEntries = (int)(kGaussHi - kGaussLo) + 1;
+struct GaussTableData { float h[kGaussEntries]; float pair[2 * kGaussEntries]; };
+constexpr GaussTableData make_gauss_table() {
+  GaussTableData t = {};
+  for (int i = 0; i < kGaussEntries; i++) {
+    const double z = (double)__builtin_bit_cast(float, (kGaussLo + (uint32_t)i) << 16);
+    const double H = 0.5 * ctmath::erf_pos(z * 0.70710678118654752440);
+    const double Q = z * ctmath::exp_neg(0.5 * z * z) * 0.39894228040143267794;
+    t.h[i] = (float)H;
+    t.pair[2 * i] = (float)H;
+    t.pair[2 * i + 1] = (float)Q;
+  }
+  return t;
+}
+__device__ const GaussTableData g_gauss_table = make_gauss_table();
+
 template <bool kPair> struct GaussTable {
-  static constexpr uint32_t kLo = 0x3880u;          // bf16 bits of 2^-14
-  static constexpr uint32_t kHi = 0x417fu;          // bf16 bits of the largest bf16 number below 16
-  static constexpr int kEntries = (int)(kHi - kLo) + 1;
+  static constexpr uint32_t kLo = kGaussLo;
+  static constexpr uint32_t kHi = kGaussHi;
+  static constexpr int kEntries = kGaussEntries;
   static constexpr int kEntryBytes = kPair ? 8 : 4;
   static constexpr int kBytes = kEntries * kEntryBytes;
 
   // tbl: LDS; every thread of the workgroup calls this (followed by a barrier at the caller)
   static __device__ __forceinline__ void build(float* tbl, int tid, int nthreads) {
-    for (int i = tid; i < kEntries; i += nthreads) {
-      const double z = (double)__builtin_bit_cast(float, (kLo + (uint32_t)i) << 16);
-      const double H = 0.5 * erf(z * 0.70710678118654752440);
-      if (kPair) {
-        tbl[2 * i] = (float)H;
-        tbl[2 * i + 1] = (float)(z * exp(-0.5 * z * z) * 0.39894228040143267794);
-      } else {
-        tbl[i] = (float)H;
-      }
-    }
+    const float* src = kPair ? g_gauss_table.pair : g_gauss_table.h;
+    for (int i = tid; i < (kPair ? 2 : 1) * kEntries; i += nthreads) tbl[i] = src[i];
   }
   // LDS address of the entry for the bf16 number whose bits (sign included or not) are in the low 16 bits of
   // `bits`: clamped magnitude bits times the entry size plus origin(table address), in three instructions
