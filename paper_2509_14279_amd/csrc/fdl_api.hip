@@ -378,9 +378,20 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
     }
     if (p.pad) launch_zero_cols_bf16(dZ, M, N, p.ldz, s);   // the surplus columns enter the dX and dW contractions
   }
+  // Where the contractions below leave split reductions behind (bf16 tuned path), their sums and the column sums
+  // share one launch at the end of the pass; otherwise the column sums are finished here.
+  const bool pair_sums = p.pair && (p.pair_sa > 1 || p.pair_sb > 1);
+  const bool b4_sums = !p.pair && p.b4_fast && (p.pad || p.b4_split > 1 || p.b4_fast_rows < M);
+  const bool tail = dt == FDL_BF16 && (pair_sums || b4_sums);
+  TailSums tj = {};
+  tj.colpart = static_cast<const float*>(colpart); tj.groups = p.b1_groups; tj.N = N;
+  tj.dbeta = dbeta; tj.dgamma = dgamma; tj.db = db;
+  auto sum_later = [&](int k, const void* part, int parts, int64_t n, void* out) {
+    tj.part[k] = static_cast<const float*>(part); tj.parts[k] = parts; tj.n[k] = n; tj.out[k] = out;
+  };
   {
     PhaseTimer t(FDL_PHASE_B2, s);
-    launch_b2((int)dt, N, p.b1_groups, colpart, dbeta, dgamma, db, s);
+    if (!tail) launch_b2((int)dt, N, p.b1_groups, colpart, dbeta, dgamma, db, s);
   }
   {
     // B3: dX[M,K] = dZ[M,N] W[N,K]
@@ -388,7 +399,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
     if (p.pair) {
       // one launch for both contractions (B4 below only sums the partial sums of dW, where its reduction is split)
       launch_fast_pair(M, K, N, p.pair_sa, p.pair_sb, dZ, W, X, dX, ws + p.off_dxpart, dW, ws + p.off_dwpart, s);
-      if (p.pair_sa > 1) launch_fast_b4_reduce(K, M, p.pair_sa, ws + p.off_dxpart, dX, s);
+      if (p.pair_sa > 1) sum_later(0, ws + p.off_dxpart, p.pair_sa, M * K, dX);
     } else if (p.pad) {
       void* Wp = ws + p.off_wpad_b;
       launch_fast_pad_weights(K, N, W, nullptr, Wp, nullptr, s);
@@ -404,7 +415,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
     // B4: dW[N,K] = dZ^T[N,M] X[M,K]
     PhaseTimer t(FDL_PHASE_B4, s);
     if (p.pair) {
-      if (p.pair_sb > 1) launch_fast_b4_reduce(K, N, p.pair_sb, ws + p.off_dwpart, dW, s);
+      if (p.pair_sb > 1) sum_later(1, ws + p.off_dwpart, p.pair_sb, N * K, dW);
     } else if (p.pad && p.b4_fast) {
       // padded mode: the fast kernel writes fp32 partials of the first b4_fast_rows rows; the generic kernel adds one
       // for the remaining rows (there is always at least one when K is not a multiple of the tile)
@@ -419,7 +430,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
         launch_generic_store_f32(g, dwpart + (size_t)parts * N * K, s);
         parts++;
       }
-      launch_fast_b4_reduce(K, N, parts, dwpart, dW, s);
+      sum_later(1, dwpart, parts, N * K, dW);
     } else if (p.b4_fast) {
       // the fast kernel reduces over the first b4_fast_rows rows (a whole number of pipeline rounds); the few rows
       // after them go through the generic kernel into one more fp32 partial sum
@@ -432,12 +443,13 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
         const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
         GemmDesc g = {dZt, Xt, N, K, M - Mf, N, K, false, false, p.b4_wb};
         launch_generic_store_f32(g, dwpart + (size_t)p.b4_split * N * K, s);
-        launch_fast_b4_reduce(K, N, p.b4_split + 1, dwpart, dW, s);
       }
+      if (p.b4_split + extra > 1) sum_later(1, dwpart, p.b4_split + extra, N * K, dW);
     } else {
       GemmDesc g = {dZ, X, N, K, M, p.ldz, K, false, false, p.b4_wb};
       launch_generic_store((int)dt, g, dW, s);
     }
+    if (tail) launch_finish(tj, s);
   }
   return launch_status();
 }
@@ -606,8 +618,8 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
       const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
       GemmDesc g = {Gt, Xt, N, K, M - Mf, N, K, false, false, p.b4_wb};
       launch_generic_store_f32(g, dwpart + (size_t)p.b4_split * N * K, s);
-      launch_fast_b4_reduce(K, N, p.b4_split + 1, dwpart, dW, s);
     }
+    if (p.b4_split + extra > 1) launch_fast_b4_reduce(K, N, p.b4_split + extra, dwpart, dW, s);
   } else {
     GemmDesc g = {G, X, N, K, M, N, K, false, false, p.b4_wb};
     launch_generic_store((int)dt, g, dW, s);

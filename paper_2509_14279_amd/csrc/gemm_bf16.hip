@@ -952,7 +952,8 @@ int fast_b4_split(int64_t M, int64_t K, int64_t N) {
 
 // dW from the first M rows (a whole number of pipeline rounds, see fast_b4_rows).  With split > 1 or extra > 0 the
 // kernel writes fp32 partial sums dwpart[0 .. split); the caller may add `extra` more partials behind them (the
-// rows the fast kernel does not cover) and then calls launch_fast_b4_reduce; otherwise dW is final on return.
+// rows the fast kernel does not cover) and then sums them (launch_fast_b4_reduce, or the backward pass's finishing
+// launch); otherwise dW is final on return.
 void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, const void* X, void* dW,
                     void* dwpart, hipStream_t s) {
   FastParams p = {};
@@ -962,7 +963,6 @@ void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const
   p.nkt = (int)(M / kB4BK / split); p.split = split;
   if (split > 1 || extra > 0) launch<true, true, EPI_PARTIAL, kB4BK, stages_of(kB4BK)>(p, s);
   else launch<true, true, EPI_STORE, kB4BK, stages_of(kB4BK)>(p, s);
-  if (split > 1 && extra == 0) launch_fast_b4_reduce(K, N, split, dwpart, dW, s);
 }
 
 // Padded mode: dZ has pitch Np (zero surplus columns); X is read up to Kp columns per row, so M must be at most

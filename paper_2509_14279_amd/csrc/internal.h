@@ -118,6 +118,20 @@ void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool
                      hipStream_t s);
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
                hipStream_t s);
+// bf16: the column sums (as launch_b2) and up to two sums of fp32 split-reduction partials
+// (out[k][i] = bf16(sum over q < parts[k] of part[k][q * n[k] + i]); parts[k] = 0: none) in one launch
+struct TailSums {
+  const float* part[2];
+  int parts[2];
+  int64_t n[2];
+  void* out[2];
+  int blocks[2];          // filled in by launch_finish
+  const float* colpart;   // [groups][3][N]
+  int groups;
+  int64_t N;
+  float *dbeta, *dgamma, *db;
+};
+void launch_finish(TailSums j, hipStream_t s);
 
 // ---- sibling operators' row-wise / element-wise kernels ------------------------------------------
 void launch_layernorm(int dt, int64_t M, int64_t N, float eps, const void* A, const float* gamma, const float* beta,

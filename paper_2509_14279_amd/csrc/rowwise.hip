@@ -476,18 +476,15 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int6
 // (the phase is pure latency: a few tens of MB), fp64 sums in a fixed order.
 // (nwhich = gridDim.y kinds of partial per group, colpart [groups][nwhich][N]; kind w goes to out_w)
 template <class C>
-__global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C* __restrict__ colpart,
-                                                  float* __restrict__ dbeta, float* __restrict__ dgamma,
-                                                  float* __restrict__ db) {
+__device__ __forceinline__ void b2_columns(int64_t N, int groups, int nwhich, const C* __restrict__ colpart, int cblock,
+                                           int which, float* __restrict__ out, double (*red)[64]) {
   constexpr int kSlices = 16;
-  __shared__ double red[kSlices][64];
   const int lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
-  const int64_t col = (int64_t)blockIdx.x * 64 + lane;
-  const int which = blockIdx.y;
+  const int64_t col = (int64_t)cblock * 64 + lane;
   double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
   if (col < N) {
     const C* src = colpart + (int64_t)which * N + col;
-    const int64_t gstride = (int64_t)gridDim.y * N;
+    const int64_t gstride = (int64_t)nwhich * N;
     int g = slice;
     for (; g + 3 * kSlices < groups; g += 4 * kSlices) {
       const C v0 = src[(int64_t)g * gstride], v1 = src[(int64_t)(g + kSlices) * gstride];
@@ -502,9 +499,49 @@ __global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C
     double t = 0.0;
 #pragma unroll
     for (int w = 0; w < kSlices; w++) t += red[w][lane];
-    float* out = which == 0 ? dbeta : (which == 1 ? dgamma : db);
     out[col] = (float)t;
   }
+}
+
+template <class C>
+__global__ __launch_bounds__(1024) void b2_kernel(int64_t N, int groups, const C* __restrict__ colpart,
+                                                  float* __restrict__ dbeta, float* __restrict__ dgamma,
+                                                  float* __restrict__ db) {
+  __shared__ double red[16][64];
+  const int which = blockIdx.y;
+  b2_columns<C>(N, groups, (int)gridDim.y, colpart, (int)blockIdx.x, which,
+                which == 0 ? dbeta : (which == 1 ? dgamma : db), red);
+}
+
+// The tail of a bf16 backward pass in one launch, for shapes where the contractions leave split reductions behind:
+// workgroups [0, a.blocks) and [a.blocks, a.blocks + b.blocks) add the fp32 partial products of up to two outputs
+// (4096 elements per workgroup, partials summed in index order, one rounding to bf16), the remaining 3 ceil(N / 64)
+// workgroups finish the column sums exactly as b2_kernel does.  Small dependent launches cost a few microseconds each
+// whatever they do, which is what this saves for mid-sized layers.
+__global__ __launch_bounds__(1024) void finish_kernel(TailSums j) {
+  __shared__ double red[16][64];
+  int id = (int)blockIdx.x;
+  for (int k = 0; k < 2; k++) {
+    if (id < j.blocks[k]) {
+      const int64_t i = ((int64_t)id * 1024 + threadIdx.x) * 4;
+      if (i >= j.n[k]) return;
+      const float* part = j.part[k];
+      f32x4 acc = *reinterpret_cast<const f32x4*>(part + i);
+      for (int q = 1; q < j.parts[k]; q++) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(part + (int64_t)q * j.n[k] + i);
+        acc[0] += t[0]; acc[1] += t[1]; acc[2] += t[2]; acc[3] += t[3];
+      }
+      bf16x4 o;
+      o[0] = (bf16_t)acc[0]; o[1] = (bf16_t)acc[1]; o[2] = (bf16_t)acc[2]; o[3] = (bf16_t)acc[3];
+      *reinterpret_cast<bf16x4*>(static_cast<bf16_t*>(j.out[k]) + i) = o;
+      return;
+    }
+    id -= j.blocks[k];
+  }
+  const int cblocks = (int)((j.N + 63) / 64);
+  const int which = id / cblocks;
+  b2_columns<float>(j.N, j.groups, 3, j.colpart, id % cblocks, which,
+                    which == 0 ? j.dbeta : (which == 1 ? j.dgamma : j.db), red);
 }
 
 
@@ -876,6 +913,17 @@ void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta,
   const dim3 grid((unsigned)((N + 63) / 64), 3);
   if (dt == kF32) hipLaunchKernelGGL((b2_kernel<double>), grid, dim3(1024), 0, s, N, groups, (const double*)colpart, dbeta, dgamma, db);
   else hipLaunchKernelGGL((b2_kernel<float>), grid, dim3(1024), 0, s, N, groups, (const float*)colpart, dbeta, dgamma, db);
+}
+
+// n[k] must be multiples of 4 (they are products of tile-aligned or 8-aligned dimensions on the bf16 tuned path).
+void launch_finish(TailSums j, hipStream_t s) {
+  unsigned blocks = 0;
+  for (int k = 0; k < 2; k++) {
+    j.blocks[k] = j.parts[k] > 0 ? (int)((j.n[k] / 4 + 1023) / 1024) : 0;
+    blocks += (unsigned)j.blocks[k];
+  }
+  blocks += 3u * (unsigned)((j.N + 63) / 64);
+  hipLaunchKernelGGL(finish_kernel, dim3(blocks), dim3(1024), 0, s, j);
 }
 
 }  // namespace fdl
