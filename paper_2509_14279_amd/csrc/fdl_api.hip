@@ -120,7 +120,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   // ---- backward
   q.b1_fused = b1_fused_supported(dt, N);
   if (q.b1_fused) {
-    const int64_t want = b1_fused_groups(dt, N);
+    const int64_t want = b1_fused_groups(dt, Mp, N);
     q.b1_groups = (int)(Mp < want ? Mp : want);
     q.b1_rows_per_group = 0;
   } else {

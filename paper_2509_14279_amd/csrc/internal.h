@@ -110,7 +110,7 @@ void launch_b1b(int dt, int64_t M, int64_t N, int64_t ldz, int rows_per_group, i
                 void* colpart, hipStream_t s);
 // fused single pass (row held in registers); returns false if this N is not supported by it
 bool b1_fused_supported(int dt, int64_t N);
-int b1_fused_groups(int dt, int64_t N);   // number of row groups it should be launched with (before capping at M)
+int b1_fused_groups(int dt, int64_t M, int64_t N);   // number of row groups it should be launched with (before capping at M)
 // table: evaluate GELU from the LDS table, as the forward pass did (bf16, plan.f2_rows); else as the other kernels do
 void launch_zero_cols_bf16(void* dZ, int64_t M, int64_t N, int64_t ldz, hipStream_t s);
 void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, const void* dY, const void* Zsave,

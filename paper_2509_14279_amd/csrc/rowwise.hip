@@ -890,15 +890,21 @@ bool b1_fused_supported(int dt, int64_t N) {
   return fused_shape(N, V, V == vmax, &fs);
 }
 
-// Row groups (= workgroups) of the fused kernel.  With 1024 threads one workgroup fills a CU's register file:
-// 256 groups are then all resident at once and the rows in flight across the chip form one contiguous window
-// (measured 5 % faster than 512 groups in two batches); the smaller shapes do best with 512.
-int b1_fused_groups(int dt, int64_t N) {
+// Row groups (= workgroups) of the fused kernel.  Each group leaves 3 N partial column sums behind, so fewer groups
+// mean less traffic for the phase and for the column reduction after it, while the rows in flight (two per group)
+// must keep the memory system busy.  Measured: 256 groups are best once a row takes at least 512 lanes (with 1024
+// threads a workgroup fills a CU's register file, all groups are resident at once and the rows in flight form one
+// contiguous window); narrower rows need 512 groups, unless the matrix is so short that a group would walk fewer
+// than 8 rows.
+int b1_fused_groups(int dt, int64_t M, int64_t N) {
   const int vmax = dt == kF32 ? 4 : 8;
   const int V = (N % vmax == 0) ? vmax : 1;
   FusedShape fs;
   if (!fused_shape(N, V, V == vmax, &fs)) return 512;
-  return fs.nt == 1024 ? 256 : 512;
+  const int64_t lanes = (N + V - 1) / V;
+  int64_t groups = lanes >= 512 ? 256 : 512;
+  if (M / 8 < groups) groups = M / 8 < 256 ? 256 : M / 8;
+  return (int)groups;
 }
 
 void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, const void* dY, const void* Zsave,
