@@ -82,6 +82,8 @@ class Ceilings:
         vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
         L.fdlc_mfma_bf16.argtypes = [ci, ci, ci, vp, vp]
         L.fdlc_mfma_bf16_flop.argtypes = [ci, ci, ci]; L.fdlc_mfma_bf16_flop.restype = ctypes.c_double
+        L.fdlc_mfma_f64.argtypes = [ci, ci, vp, vp]
+        L.fdlc_mfma_f64_flop.argtypes = [ci, ci]; L.fdlc_mfma_f64_flop.restype = ctypes.c_double
         L.fdlc_stream_read.argtypes = [vp, i64, ci, vp, vp]
         L.fdlc_stream_write.argtypes = [vp, i64, ci, vp]
         L.fdlc_stream_copy.argtypes = [vp, vp, i64, ci, vp]
@@ -113,6 +115,12 @@ class Ceilings:
         out = self.torch.zeros(4, device="cuda")
         ms = self._time(lambda: self.L.fdlc_mfma_bf16(self.cus, waves, iters, out.data_ptr(), self.stream), reps)
         return self.L.fdlc_mfma_bf16_flop(self.cus, waves, iters) / (ms * 1e-3) / 1e12
+
+    def mfma_f64(self, iters=5000, reps=5):
+        """TFLOP/s of v_mfma_f64_16x16x4_f64 from registers, one wavefront per SIMD on every CU."""
+        out = self.torch.zeros(4, device="cuda")
+        ms = self._time(lambda: self.L.fdlc_mfma_f64(self.cus, iters, out.data_ptr(), self.stream), reps)
+        return self.L.fdlc_mfma_f64_flop(self.cus, iters) / (ms * 1e-3) / 1e12
 
     def lds_table(self, offsets, kind=16, iters=20000):
         """Shader cycles per read instruction and wave for an arbitrary lane -> byte-offset table [8][64]."""
@@ -198,6 +206,7 @@ def run_ceilings(lane_groups: bool = True):
           f" x {clk:.2f} GHz = {prop.multi_processor_count * 4 * 1024 * clk / 1e3:.0f} TFLOP/s; published 2500 TFLOP/s")
     for w in (4, 8):
         print(f"mfma_bf16 registers only, {w // 4} wave(s) per SIMD: {c.mfma_bf16(waves=w):8.1f} TFLOP/s")
+    print(f"mfma_f64 (16x16x4) registers only, 1 wave per SIMD: {c.mfma_f64():8.1f} TFLOP/s; published 78.6 TFLOP/s")
     st = c.streams()
     for k in ("read", "write", "copy", "mix21"):
         print(f"stream {k:6s} 1 GiB buffers, 16 B per lane, non-temporal, best of 4 grids: {st[k]:8.1f} GB/s")
@@ -222,7 +231,7 @@ def run_ceilings(lane_groups: bool = True):
         print(f"  {name}: {len(groups)} group(s) of {len(groups[0])} lanes; cycles/read/wave {base:.2f} without, {hi:.2f} with a conflicting pair")
         for g in groups:
             print(f"      lanes {ranges(g)}")
-    out = {"mfma_bf16_tflops": round(c.mfma_bf16(waves=4), 1), **{f"stream_{k}_gbs": round(v, 1) for k, v in st.items()}}
+    out = {"mfma_bf16_tflops": round(c.mfma_bf16(waves=4), 1), "mfma_f64_tflops": round(c.mfma_f64(), 1), **{f"stream_{k}_gbs": round(v, 1) for k, v in st.items()}}
     print("CEILINGS_JSON: " + json.dumps(out))
 
 
@@ -605,16 +614,17 @@ def main():
         for e in s:
             ev.destroy(e)
 
-    # ---- the machine's own ceilings, measured now on this GPU (bf16 workloads)
+    # ---- the machine's own ceilings, measured now on this GPU
     ceil = None
-    if cfg.dtype == "bf16" and not args.no_ceilings:
+    mkey = "mfma_bf16_TFLOP/s" if cfg.dtype == "bf16" else "mfma_f64_TFLOP/s"
+    if not args.no_ceilings:
         try:
             c = Ceilings(ev)
             st = c.streams(reps=3)
-            ceil = {"mfma_bf16_TFLOP/s": round(c.mfma_bf16(iters=10000, reps=3), 1),
+            ceil = {mkey: round(c.mfma_bf16(iters=10000, reps=3) if cfg.dtype == "bf16" else c.mfma_f64(iters=3000, reps=3), 1),
                     "stream_read_GB/s": round(st["read"], 1), "stream_write_GB/s": round(st["write"], 1),
                     "stream_copy_GB/s": round(st["copy"], 1), "stream_2reads_1write_GB/s": round(st["mix21"], 1),
-                    "how": "register-resident v_mfma_f32_32x32x16_bf16 loop on every CU; 1 GiB streaming kernels, best of 4 grids"}
+                    "how": "register-resident MFMA loop on every CU (v_mfma_f32_32x32x16_bf16, or v_mfma_f64_16x16x4_f64 for fp32 storage); 1 GiB streaming kernels, best of 4 grids"}
         except Exception as e:   # the ceilings are context: never fail the benchmark on them
             ceil = {"error": repr(e)[:200]}
 
@@ -626,8 +636,8 @@ def main():
         if kind == "flop":
             ent["TFLOP/s"] = round(amount / (ms * 1e-3) / 1e12, 2)
             ent["frac_mfma_peak"] = round(ent["TFLOP/s"] / PEAK_TFLOPS[cfg.dtype], 4)
-            if ceil and "mfma_bf16_TFLOP/s" in ceil:
-                ent["frac_measured"] = round(ent["TFLOP/s"] / ceil["mfma_bf16_TFLOP/s"], 4)
+            if ceil and mkey in ceil:
+                ent["frac_measured"] = round(ent["TFLOP/s"] / ceil[mkey], 4)
         elif amount > 0:
             ent["GB/s"] = round(amount / (ms * 1e-3) / 1e9, 1)
             ent["frac_hbm_peak"] = round(ent["GB/s"] / PEAK_HBM_GBS, 4)
@@ -642,9 +652,9 @@ def main():
         ach = amount / (phase_ms[dom] * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_TFLOPS[cfg.dtype],
                     "unit": "TFLOP/s", "frac": round(ach / PEAK_TFLOPS[cfg.dtype], 4), "traffic": measured_traffic(cfg.name, dom)}
-        if ceil and "mfma_bf16_TFLOP/s" in ceil:
-            roofline["measured_peak"] = ceil["mfma_bf16_TFLOP/s"]
-            roofline["frac_of_measured"] = round(ach / ceil["mfma_bf16_TFLOP/s"], 4)
+        if ceil and mkey in ceil:
+            roofline["measured_peak"] = ceil[mkey]
+            roofline["frac_of_measured"] = round(ach / ceil[mkey], 4)
     else:
         ach = amount / (phase_ms[dom] * 1e-3) / 1e9
         roofline = {"kernel": dom, "bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",

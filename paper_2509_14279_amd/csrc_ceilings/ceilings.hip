@@ -3,6 +3,7 @@
 // (libfdl_ceilings.so), never linked into libfdl.so.  C ABI; every call enqueues kernels on the given stream.
 //
 //   fdlc_mfma_bf16      register-resident v_mfma_f32_32x32x16_bf16 loop, one or two waves per SIMD on every CU
+//   fdlc_mfma_f64       the same for v_mfma_f64_16x16x4_f64 (the fp32-storage path's instruction)
 //   fdlc_stream_*       read-only / write-only / copy / two-reads-one-write over large buffers, 16 bytes per lane,
 //                       non-temporal
 //   fdlc_lds_probe      one LDS read instruction in a tight loop with a chosen lane -> address pattern, timed with the
@@ -60,6 +61,41 @@ void mfma_bf16_kernel(int iters, float* out) {
     for (int j = 0; j < NB; j++)
       for (int r = 0; r < 16; r++) s += acc[i][j][r];
   if (s == 123.456f) out[0] = s;   // keeps the loop alive; practically never true
+}
+
+// The fp32-storage path's instruction: v_mfma_f64_16x16x4_f64, 4 x 4 independent accumulator blocks per wave (the
+// generic kernel has 2 x 2 with four reduction steps each), one wave per SIMD.
+__global__ __launch_bounds__(256) void mfma_f64_kernel(int iters, float* out) {
+  typedef __attribute__((ext_vector_type(4))) double f64x4;
+  double a[4], b[4];
+  for (int i = 0; i < 4; i++) { a[i] = (double)(float)pseudo(threadIdx.x * 4 + i); b[i] = (double)(float)pseudo(0x10000u + threadIdx.x * 4 + i); }
+  f64x4 acc[4][4];
+  for (int i = 0; i < 4; i++)
+    for (int j = 0; j < 4; j++)
+      for (int r = 0; r < 4; r++) acc[i][j][r] = 0.0;
+#pragma unroll
+  for (int i = 0; i < 4; i++)
+#pragma unroll
+    for (int j = 0; j < 4; j++) asm volatile("" : "+a"(acc[i][j]));
+  for (int it = 0; it < iters; it++) {
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[i], b[j], acc[i][j], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; i++) asm volatile("" : "+v"(a[i]));
+    // the accumulators stay in AGPRs from one round to the next (left to itself the compiler moves all 128 registers
+    // to VGPRs and back in every round, and the loop then measures those moves: 36 instead of 77 TFLOP/s)
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+      for (int j = 0; j < 4; j++) asm volatile("" : "+a"(acc[i][j]));
+  }
+  double s = 0.0;
+  for (int i = 0; i < 4; i++)
+    for (int j = 0; j < 4; j++)
+      for (int r = 0; r < 4; r++) s += acc[i][j][r];
+  if (s == 123.456) out[0] = (float)s;
 }
 
 // ---------------------------------------------------------------------------------------------- streaming
@@ -276,6 +312,13 @@ FDLC_API int fdlc_mfma_bf16(int grid, int waves, int iters, float* out, void* st
 FDLC_API double fdlc_mfma_bf16_flop(int grid, int waves, int iters) {
   return (double)grid * waves * iters * (waves == 4 ? 16.0 : 8.0) * (2.0 * 32 * 32 * 16);
 }
+// iters rounds of 16 v_mfma_f64_16x16x4_f64 per wave, grid workgroups of four wavefronts
+FDLC_API int fdlc_mfma_f64(int grid, int iters, float* out, void* stream) {
+  if (grid < 1 || iters < 1 || out == nullptr) return 1;
+  hipLaunchKernelGGL(mfma_f64_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, iters, out);
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+FDLC_API double fdlc_mfma_f64_flop(int grid, int iters) { return (double)grid * 4 * iters * 16.0 * (2.0 * 16 * 16 * 4); }
 FDLC_API int fdlc_stream_read(const void* src, int64_t bytes, int grid, void* sink, void* stream) {
   if (!src || !sink || bytes < 16 || bytes % 16 || grid < 1) return 1;
   hipLaunchKernelGGL(stream_read_kernel, dim3(grid), dim3(kStreamThreads), 0, (hipStream_t)stream, (const u32x4*)src, bytes / 16, (uint32_t*)sink);
