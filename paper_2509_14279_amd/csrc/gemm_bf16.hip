@@ -941,13 +941,27 @@ void launch_fast_b3_padded(int64_t M, int64_t K, int64_t N, const void* dZ, cons
   launch<true, false, EPI_STORE, kB3BK, stages_of(kB3BK), true, true>(p, s);
 }
 
-// Split of the reduction over M so that small dW outputs still fill the chip: each part keeps >= 512 rows.
+// Split of the reduction over M.  One workgroup per compute unit walks the (tile, part) units of its part, so the
+// kernel takes ceil(tiles * split / CUs) rounds of M / split rows each: a small dW fills the chip only when split,
+// and a dW with a few tiles more than a whole number of rounds (9 x 32 = 288 tiles on 256 compute units: two rounds,
+// the second nearly empty) loses up to half its time unless the rounds are made shorter.  Against that stands the
+// traffic of the fp32 partial sums (written, read again and summed).  Both are priced with round figures for this
+// part - 23 ns per reduction row and round, 4 TB/s for the partial sums - and the cheapest split wins; each part keeps
+// at least 512 rows and a whole number of pipeline rounds, and the partial sums at most 512 MB.
 int fast_b4_split(int64_t M, int64_t K, int64_t N) {
   const int64_t tiles = ((K + kTile - 1) / kTile) * ((N + kTile - 1) / kTile);
   const int64_t unit = (int64_t)kB4BK * stages_of(kB4BK);   // every part is a whole number of slice groups
-  int split = 1;
-  while (tiles * split * 2 <= kPlanCUs && M % (split * 2 * unit) == 0 && M / (split * 2) >= 512) split *= 2;
-  return split;   // M: the rows the fast kernel covers
+  int best = 1;
+  double best_cost = 0.0;
+  for (int split = 1; split <= 16; split *= 2) {
+    if (split > 1 && (M % (split * unit) != 0 || M / split < 512)) break;
+    const double partial_bytes = split > 1 ? (double)split * (double)tiles * kTile * kTile * 4.0 : 0.0;
+    if (partial_bytes > 512.0 * 1024 * 1024) break;
+    const int64_t rounds = (tiles * split + kPlanCUs - 1) / kPlanCUs;
+    const double cost = (double)rounds * (double)(M / split) * 23e-9 + 2.0 * partial_bytes / 4e12;
+    if (split == 1 || cost < 0.97 * best_cost) { best = split; best_cost = cost; }
+  }
+  return best;   // M: the rows the fast kernel covers
 }
 
 // dW from the first M rows (a whole number of pipeline rounds, see fast_b4_rows).  With split > 1 or extra > 0 the
