@@ -351,6 +351,7 @@ SWEEP_SHAPES = [
     ("untuned", "bf16", 32768, 1024, 1024), ("untuned", "bf16", 16384, 1536, 3072), ("untuned", "bf16", 4096, 4096, 16384),
     ("untuned", "bf16", 2048, 8192, 512), ("untuned", "bf16", 131072, 512, 2048), ("untuned", "bf16", 8192, 2048, 32768),
     ("untuned", "bf16", 10000, 1024, 3072), ("untuned", "bf16", 50001, 2048, 4096), ("untuned", "bf16", 10000, 1000, 3000), ("untuned", "bf16", 16384, 1024, 64), ("untuned", "bf16", 4096, 1024, 8192), ("untuned", "bf16", 4096, 1024, 8200),
+    ("untuned", "bf16", 65536, 2304, 8192), ("untuned", "bf16", 3001, 771, 1537),
     ("tuned", "f32", 3001, 771, 1537), ("untuned", "f32", 4096, 1024, 2048),
 ]
 

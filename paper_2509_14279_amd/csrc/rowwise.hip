@@ -17,25 +17,46 @@ namespace {
 
 // ------------------------------------------------------------------------------------------------
 // FS: merge per-(row, column tile) partial (mean, sum of squared deviations) pairs with the pairwise
-// update of Chan et al., in fp64; one thread per row.  part is [tiles][M].
+// update of Chan et al., in fp64.  part is [tiles][M].  Sixteen lanes share a row: lane l merges tiles l, l + 16, ...
+// in order, then the sixteen (count, mean, M2) triples are merged pairwise across the lanes - the update is
+// associative, and with one thread per row a matrix of a few thousand rows kept a dozen workgroups busy with a
+// serial chain of fp64 divisions per tile.
+struct Moments { double n, mu, m2; };
+__device__ __forceinline__ Moments merge_moments(const Moments& a, const Moments& b) {
+  Moments r;
+  r.n = a.n + b.n;
+  const double d = b.mu - a.mu, w = r.n > 0.0 ? b.n / r.n : 0.0;
+  r.mu = a.mu + d * w;
+  r.m2 = a.m2 + b.m2 + d * d * a.n * w;
+  return r;
+}
 __global__ __launch_bounds__(256) void stats_finalize_kernel(const f32x2* __restrict__ part, int tiles, int tile_w,
                                                              int64_t M, int64_t N, float eps,
                                                              float* __restrict__ mean, float* __restrict__ rstd) {
-  const int64_t m = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (m >= M) return;
-  double na = 0.0, mu = 0.0, m2 = 0.0;
-  for (int t = 0; t < tiles; t++) {
+  constexpr int kLanes = 16;
+  const int l = threadIdx.x & (kLanes - 1);
+  const int64_t m = (int64_t)blockIdx.x * (256 / kLanes) + (threadIdx.x / kLanes);
+  const int64_t mc = m < M ? m : M - 1;      // lanes past the last row redo it (no early exit before the shuffles)
+  Moments acc = {0.0, 0.0, 0.0};
+  for (int t = l; t < tiles; t += kLanes) {
     int64_t nb = N - (int64_t)t * tile_w;
     if (nb <= 0) break;
     if (nb > tile_w) nb = tile_w;
-    const f32x2 p = part[(int64_t)t * M + m];
-    const double d = (double)p[0] - mu, n = na + (double)nb;
-    mu += d * (double)nb / n;
-    m2 += (double)p[1] + d * d * na * (double)nb / n;
-    na = n;
+    const f32x2 p = part[(int64_t)t * M + mc];
+    const Moments x = {(double)nb, (double)p[0], (double)p[1]};
+    acc = merge_moments(acc, x);
   }
-  mean[m] = (float)mu;
-  rstd[m] = (float)(1.0 / sqrt(m2 / (double)N + (double)eps));
+#pragma unroll
+  for (int k = 1; k < kLanes; k <<= 1) {
+    Moments o;
+    o.n = __shfl_xor(acc.n, k, kWave); o.mu = __shfl_xor(acc.mu, k, kWave); o.m2 = __shfl_xor(acc.m2, k, kWave);
+    // both lanes of a pair merge the same two triples in the same order (lower lane's first)
+    acc = (l & k) ? merge_moments(o, acc) : merge_moments(acc, o);
+  }
+  if (l == 0 && m < M) {
+    mean[m] = (float)acc.mu;
+    rstd[m] = (float)(1.0 / sqrt(acc.m2 / (double)N + (double)eps));
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -728,7 +749,7 @@ template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int64_t ld
 
 void launch_stats_finalize(const void* part, int tiles, int tile_w, int64_t M, int64_t N, float eps, float* mean,
                            float* rstd, hipStream_t s) {
-  const unsigned blocks = (unsigned)((M + 255) / 256);
+  const unsigned blocks = (unsigned)((M + 15) / 16);   // sixteen lanes per row
   hipLaunchKernelGGL(stats_finalize_kernel, dim3(blocks), dim3(256), 0, s, (const f32x2*)part, tiles, tile_w, M, N, eps,
                      mean, rstd);
 }
