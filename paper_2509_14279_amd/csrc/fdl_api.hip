@@ -115,6 +115,11 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.off_xtail = off; off += align256(q.pad ? fast_padded_tail_bytes(K) : (q.f1_fast ? fast_f1_tail_bytes(M, K) : 0));
   q.off_wpad_f = off; off += align256(q.pad ? (size_t)Np * Kp * 2 : 0);
   q.off_bpad_f = off; off += align256(q.pad ? (size_t)Np * 4 : 0);
+  // Large batches on the tuned kernel (tile-aligned N and K): the weights are transposed first, 4 N K bytes of traffic
+  // against about 6 % of the contraction's time; that pays from roughly 10^4 rows, with a margin for the extra launch.
+  q.fwd_bytes_plain = off;
+  q.f1_wt = q.f1_fast && !q.pad && M >= 32768;
+  q.off_wt = off; off += align256(q.f1_wt ? (size_t)N * K * 2 : 0);
   q.fwd_bytes = off;
 
   // ---- backward
@@ -265,7 +270,9 @@ static fdl_status forward_launches(const Plan& p, const void* X, const void* W, 
       launch_fast_pad_weights(K, N, W, b, Wp, bp, s);
       launch_fast_f1_padded(M, K, N, X, Wp, bp, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
     } else if (p.f1_fast) {
-      launch_fast_f1(M, K, N, X, W, b, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
+      void* Wt = p.f1_wt ? ws + p.off_wt : nullptr;
+      if (p.f1_wt) launch_fast_transpose(N, K, W, Wt, s);
+      launch_fast_f1(M, K, N, X, W, Wt, b, Zsave, p.f2_rows ? nullptr : part, ws + p.off_xtail, s);
     } else {
       GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
       launch_generic_f1(p.dt, g, b, Zsave, part, s);
@@ -327,6 +334,9 @@ extern "C" fdl_status fdl_forward_static(fdl_dtype dt, int64_t M, int64_t K, int
   Plan p;
   const fdl_status st = check_forward_args(dt, M, K, N, X, W, b, gamma, beta, eps, Y, Zsave, mean, rstd, &p);
   if (st != FDL_OK) return st;
+  if (p.fwd_bytes > (size_t)FDL_STATIC_SCRATCH_BYTES && p.f1_wt) {
+    p.f1_wt = 0; p.fwd_bytes = p.fwd_bytes_plain;   // no room for the transposed weights: the kernel reads W as it is
+  }
   if (p.fwd_bytes > (size_t)FDL_STATIC_SCRATCH_BYTES) return FDL_ERR_WORKSPACE;   // the problem needs more than the array holds
   if (!forward_args_aligned(X, W, b, gamma, beta, Y, Zsave, mean, rstd)) return FDL_ERR_ALIGN;
   if (M == 0) return FDL_OK;

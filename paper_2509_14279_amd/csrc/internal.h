@@ -30,7 +30,10 @@ struct Plan {
   int stat_tile_w;        // width of one partial-statistics column tile
   int stat_tiles;         // number of such tiles per row
   size_t off_part;        // float2 [stat_tiles][M]
-  size_t fwd_bytes;
+  int f1_wt;              // 1: the fast kernel reads the weights from a transposed copy (large batches)
+  size_t off_wt;          // bf16 [K][N], the last region of the forward workspace
+  size_t fwd_bytes;       // (without the transposed weights: fwd_bytes - align256(N K 2), see fwd_bytes_plain)
+  size_t fwd_bytes_plain; // forward workspace of the same plan with f1_wt = 0
   // backward
   int b1_fused;           // 1: one pass with the row held in registers; 0: B1a + B1b
   int b1_groups;          // number of row groups that produce column partials
@@ -150,8 +153,10 @@ bool fast_b4_supported(int64_t M, int64_t K, int64_t N);
 int64_t fast_b4_rows(int64_t M);
 int fast_f1_stat_tile_w();
 size_t fast_f1_tail_bytes(int64_t M, int64_t K);
-void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const float* bias, void* Zsave,
-                    void* part, void* xtail, hipStream_t s);
+// Wt: null, or the transposed weights [K][N] from launch_fast_transpose (N, K multiples of 64)
+void launch_fast_transpose(int64_t N, int64_t K, const void* W, void* Wt, hipStream_t s);
+void launch_fast_f1(int64_t M, int64_t K, int64_t N, const void* X, const void* W, const void* Wt, const float* bias,
+                    void* Zsave, void* part, void* xtail, hipStream_t s);
 // padded mode (N, K multiples of 8 but not both of 256): see gemm_bf16.hip
 bool fast_padded_supported(int64_t M, int64_t K, int64_t N);
 int64_t fast_pad_dim(int64_t n);

@@ -1,6 +1,7 @@
 """fdl_forward_static (the forward pass on the library's own fixed scratch array, for callers that cannot allocate)
 against fdl_forward on the same inputs: same kernels on a different scratch address, so every output must agree bit
-for bit (stricter than the parity bars, which the fdl_forward side is held to against the oracle elsewhere).
+for bit (stricter than the parity bars, which the fdl_forward side is held to against the oracle elsewhere) - except
+where the array is too small for the transposed weights that fdl_forward uses for large batches (own test below).
 
 Two calls in a row on one GPU, the second with a smaller input, through shapes whose forward pass really uses the
 scratch: partial row statistics from the GEMM epilogue (rows longer than the row-resident normalisation holds, and the
@@ -41,7 +42,8 @@ def test_forward_static_matches_forward_on_two_calls_in_a_row():
     cases = [I.custom("bf16", 385, 512, 8448, seed=51),     # fast path, ragged M (padded X tail) + epilogue partials
              I.custom("f32", 130, 70, 200, seed=52),        # generic kernel partials, smaller
              I.custom("bf16", 300, 256, 512, seed=53),      # fast path, ragged M, row-resident normalisation
-             I.custom("bf16", 200, 136, 264, seed=54)]      # padded mode: zero-padded weight copy + X tail in the scratch
+             I.custom("bf16", 200, 136, 264, seed=54),      # padded mode: zero-padded weight copy + X tail in the scratch
+             I.custom("bf16", 32768, 128, 256, seed=55)]    # large batch: transposed weights in the scratch
     inputs = [I.generate(c, with_dY=False) for c in cases]
     got = []
     for c, t in zip(cases, inputs):                          # the static calls back to back, nothing in between
@@ -54,6 +56,21 @@ def test_forward_static_matches_forward_on_two_calls_in_a_row():
         for k in FWD_OUT:
             assert torch.equal(g[k].view(torch.uint8), ref[k].view(torch.uint8)), (c.name, k)
             assert torch.isfinite(g[k].float()).all(), (c.name, k)
+
+
+def test_forward_static_with_weights_too_large_to_transpose_in_the_array():
+    # 32768 rows: fdl_forward transposes W into its workspace (2 N K = 17.8 MB here); the array has no room for that,
+    # so the static entry point runs the same contraction on W as it is.  Different kernels: compared to the parity
+    # bar of bf16 storage rather than bit for bit.
+    c = I.custom("bf16", 32768, 2048, 4352, seed=56)
+    assert 2 * c.N * c.K > api.FDL_STATIC_SCRATCH_BYTES
+    t = I.generate(c, with_dY=False)
+    got = run_forward(c, t, static=True)
+    ref = run_forward(c, t, static=False)
+    for k in FWD_OUT:
+        g, r = got[k].float(), ref[k].float()
+        assert torch.isfinite(g).all(), k
+        assert (g - r).abs().max().item() <= 2e-2 * r.abs().max().item(), k
 
 
 def test_forward_static_rejects_what_the_array_cannot_hold():
