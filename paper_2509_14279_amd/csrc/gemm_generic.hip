@@ -35,6 +35,7 @@ struct GemmParams {
   const void* aux;       // [I][J] in the storage type (EPI_MASK)
   int64_t I, J, R, lda, ldb;
   int a_vec, b_vec;
+  int wide;              // both contiguous extents hold at least one chunk of four: ragged rows take vector loads too
 };
 
 template <class AccT> struct Mma;
@@ -90,10 +91,25 @@ template <> __device__ __forceinline__ void load4<bf16_t>(const bf16_t* p, float
   v[0] = (float)t[0]; v[1] = (float)t[1]; v[2] = (float)t[2]; v[3] = (float)t[3];
 }
 
+// the same from an address that is only element-aligned (rows of a ragged matrix start anywhere): the compiler picks
+// the widest load the target allows for the stated alignment
+template <class T> __device__ __forceinline__ void load4u(const T* p, float (&v)[4]);
+template <> __device__ __forceinline__ void load4u<float>(const float* p, float (&v)[4]) {
+  typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));
+  const f32x4_u t = *reinterpret_cast<const f32x4_u*>(p);
+  v[0] = t[0]; v[1] = t[1]; v[2] = t[2]; v[3] = t[3];
+}
+template <> __device__ __forceinline__ void load4u<bf16_t>(const bf16_t* p, float (&v)[4]) {
+  typedef __bf16 bf16x4_u __attribute__((ext_vector_type(4), aligned(2)));
+  const bf16x4_u t = *reinterpret_cast<const bf16x4_u*>(p);
+  v[0] = (float)t[0]; v[1] = (float)t[1]; v[2] = (float)t[2]; v[3] = (float)t[3];
+}
+
 // One operand's BT x 16 slice: global -> registers -> LDS, and LDS -> MFMA fragments.
 // RC  (reduction-contiguous in memory): LDS layout [BT][20] floats (16 + 4 pad: 16-byte accesses of 8
 //      consecutive rows fall on 8 disjoint groups of 4 banks).
 // !RC (row index is the reduction index): LDS layout [16][BT+4] floats.
+enum { kElements = 0, kVecAligned = 1, kVecAnywhere = 2 };   // how an operand's chunks of four elements are loaded
 template <class T, bool RC, int BT> struct Operand {
   static constexpr int kChunks = BT * 16 / 4;
   static constexpr int kPerThread = kChunks / 256;
@@ -104,10 +120,13 @@ template <class T, bool RC, int BT> struct Operand {
   // column inside it (always valid memory) and replaced by zero when the slice goes to LDS.  A load under a
   // per-lane branch, or one merged with a zero in its destination register, would make the wavefront wait for
   // every load in flight first, which serialises the slices' trips to memory.
-  // vec: 16-byte (fp32) or 8-byte (bf16) loads - base and pitch aligned and the contiguous extent a multiple of 4,
-  // so a chunk is inside the matrix entirely or not at all.
+  // mode kVecAligned: 16-byte (fp32) or 8-byte (bf16) loads - base and pitch aligned and the contiguous extent a
+  //   multiple of 4, so a chunk is inside the matrix entirely or not at all.
+  // mode kVecAnywhere: the same loads from element-aligned addresses (ragged pitch); a chunk that straddles the end
+  //   of its row is read from the last four elements of the row instead and shifted back when it is stashed.
+  // mode kElements: one load per element (a contiguous extent below 4).
   static __device__ __forceinline__ void fetch(const T* base, int64_t ld, int64_t i0, int64_t I, int64_t r0, int64_t R,
-                                               bool vec, int tid, float (&reg)[kPerThread][4]) {
+                                               int mode, int tid, float (&reg)[kPerThread][4]) {
 #pragma unroll
     for (int q = 0; q < kPerThread; q++) {
       const int c = tid + q * 256;
@@ -116,8 +135,10 @@ template <class T, bool RC, int BT> struct Operand {
       const int64_t col = RC ? r0 + (c & 3) * 4 : i0 + (c % (BT / 4)) * 4;
       const int64_t rows = RC ? I : R, cols = RC ? R : I;
       const T* prow = base + (row < rows ? row : rows - 1) * ld;
-      if (vec) {
+      if (mode == kVecAligned) {
         load4<T>(prow + (col + 3 < cols ? col : cols - 4), reg[q]);
+      } else if (mode == kVecAnywhere) {
+        load4u<T>(prow + (col + 3 < cols ? col : cols - 4), reg[q]);
       } else {
 #pragma unroll
         for (int e = 0; e < 4; e++) reg[q][e] = to_f32<T>(prow[col + e < cols ? col + e : cols - 1]);
@@ -127,16 +148,25 @@ template <class T, bool RC, int BT> struct Operand {
 
   // r0: first reduction index of the slice that `reg` holds
   static __device__ __forceinline__ void stash(float* lds, int tid, int64_t i0, int64_t I, int64_t r0, int64_t R,
-                                               const float (&reg)[kPerThread][4]) {
+                                               int mode, const float (&reg)[kPerThread][4]) {
 #pragma unroll
     for (int q = 0; q < kPerThread; q++) {
       const int c = tid + q * 256;
       const int64_t row = RC ? i0 + (c >> 2) : r0 + c / (BT / 4);
       const int64_t col = RC ? r0 + (c & 3) * 4 : i0 + (c % (BT / 4)) * 4;
       const int64_t rows = RC ? I : R, cols = RC ? R : I;
+      // kVecAnywhere: the chunk was read `shift` elements early where it straddles the end of the row
+      const int shift = (mode == kVecAnywhere && col + 3 >= cols) ? (int)(col - (cols - 4)) : 0;
       f32x4 t;
 #pragma unroll
-      for (int e = 0; e < 4; e++) t[e] = (row < rows && col + e < cols) ? reg[q][e] : 0.0f;
+      for (int e = 0; e < 4; e++) {
+        float v = reg[q][e];
+        if (mode == kVecAnywhere) {
+#pragma unroll
+          for (int h = 1; e + h < 4; h++) v = shift == h ? reg[q][e + h] : v;
+        }
+        t[e] = (row < rows && col + e < cols) ? v : 0.0f;
+      }
       if (RC) {
         *reinterpret_cast<f32x4*>(lds + (c >> 2) * 20 + (c & 3) * 4) = t;
       } else {
@@ -162,9 +192,9 @@ template <class T, bool RC, int BT> struct Operand {
 // a trip to memory, and shapes with few tiles per compute unit have no other wavefronts to hide it behind.  LDS stays
 // double-buffered.  The body has no branches: past the last slice the loop re-fetches and re-stashes the last slice
 // (into the LDS buffer that is not read again) instead of testing, so that the compiler can count the loads in flight
-// exactly and wait only for the oldest.  VEC: both operands qualify for vector loads (a compile-time property of the
-// loop for the same reason).
-template <class T, class AccT, bool A_RC, bool B_RC, int WB, bool VEC>
+// exactly and wait only for the oldest.  MODE: how both operands are loaded (see Operand; a compile-time property of
+// the loop for the same reason).
+template <class T, class AccT, bool A_RC, bool B_RC, int WB, int MODE>
 __device__ __forceinline__ void generic_mainloop(const GemmParams& p, int64_t i0, int64_t j0, float (*lds)[2][32 * WB * 20],
                                                  typename Mma<AccT>::acc_t (&acc)[WB][WB]) {
   constexpr int BT = 32 * WB;
@@ -181,18 +211,18 @@ __device__ __forceinline__ void generic_mainloop(const GemmParams& p, int64_t i0
 #pragma unroll
   for (int d = 0; d < kDepth - 1; d++) {
     const int64_t r0 = (d < last ? d : last) * 16;
-    OpA::fetch(A, p.lda, i0, p.I, r0, p.R, VEC, tid, ra[d]);
-    OpB::fetch(B, p.ldb, j0, p.J, r0, p.R, VEC, tid, rb[d]);
+    OpA::fetch(A, p.lda, i0, p.I, r0, p.R, MODE, tid, ra[d]);
+    OpB::fetch(B, p.ldb, j0, p.J, r0, p.R, MODE, tid, rb[d]);
   }
-  OpA::stash(lds[0][0], tid, i0, p.I, 0, p.R, ra[0]);
-  OpB::stash(lds[0][1], tid, j0, p.J, 0, p.R, rb[0]);
+  OpA::stash(lds[0][0], tid, i0, p.I, 0, p.R, MODE, ra[0]);
+  OpB::stash(lds[0][1], tid, j0, p.J, 0, p.R, MODE, rb[0]);
   __syncthreads();
 
   auto step = [&](int64_t kt, int d) __attribute__((always_inline)) {
     const int cur = (int)(kt & 1);
     const int64_t rf = (kt + kDepth - 1 < last ? kt + kDepth - 1 : last) * 16;
-    OpA::fetch(A, p.lda, i0, p.I, rf, p.R, VEC, tid, ra[(d + kDepth - 1) % kDepth]);
-    OpB::fetch(B, p.ldb, j0, p.J, rf, p.R, VEC, tid, rb[(d + kDepth - 1) % kDepth]);
+    OpA::fetch(A, p.lda, i0, p.I, rf, p.R, MODE, tid, ra[(d + kDepth - 1) % kDepth]);
+    OpB::fetch(B, p.ldb, j0, p.J, rf, p.R, MODE, tid, rb[(d + kDepth - 1) % kDepth]);
     float fa[WB][4], fb[WB][4];
 #pragma unroll
     for (int a = 0; a < WB; a++) OpA::frag(lds[cur][0], wi * 16 * WB + a * 16 + l16, g, fa[a]);
@@ -209,8 +239,8 @@ __device__ __forceinline__ void generic_mainloop(const GemmParams& p, int64_t i0
 #pragma unroll
       for (int b = 0; b < WB; b++) asm volatile("" : "+a"(acc[a][b]));
     const int64_t rs = (kt + 1 < last ? kt + 1 : last) * 16;
-    OpA::stash(lds[cur ^ 1][0], tid, i0, p.I, rs, p.R, ra[(d + 1) % kDepth]);
-    OpB::stash(lds[cur ^ 1][1], tid, j0, p.J, rs, p.R, rb[(d + 1) % kDepth]);
+    OpA::stash(lds[cur ^ 1][0], tid, i0, p.I, rs, p.R, MODE, ra[(d + 1) % kDepth]);
+    OpB::stash(lds[cur ^ 1][1], tid, j0, p.J, rs, p.R, MODE, rb[(d + 1) % kDepth]);
     __syncthreads();
   };
 #pragma unroll
@@ -246,8 +276,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
 #pragma unroll
       for (int r = 0; r < 4; r++) acc[a][b][r] = 0;
 
-  if (p.a_vec && p.b_vec) generic_mainloop<T, AccT, A_RC, B_RC, WB, true>(p, i0, j0, lds, acc);
-  else generic_mainloop<T, AccT, A_RC, B_RC, WB, false>(p, i0, j0, lds, acc);
+  if (p.a_vec && p.b_vec) generic_mainloop<T, AccT, A_RC, B_RC, WB, kVecAligned>(p, i0, j0, lds, acc);
+  else if (p.wide) generic_mainloop<T, AccT, A_RC, B_RC, WB, kVecAnywhere>(p, i0, j0, lds, acc);
+  else generic_mainloop<T, AccT, A_RC, B_RC, WB, kElements>(p, i0, j0, lds, acc);
 
   // ------------------------------------------------------------------ epilogue
   // accumulator element r of block (a, b): output row iw + 16 a + row(lane, r), column jw + 16 b + col(lane, r)
@@ -359,6 +390,7 @@ void set_vec(GemmParams* p, const GemmDesc& g, bool a_rc, bool b_rc, size_t elem
   const int64_t a_extent = a_rc ? g.R : g.I, b_extent = b_rc ? g.R : g.J;
   p->a_vec = ((uintptr_t)g.A % chunk_bytes == 0) && (g.lda % 4 == 0) && (a_extent % 4 == 0);
   p->b_vec = ((uintptr_t)g.B % chunk_bytes == 0) && (g.ldb % 4 == 0) && (b_extent % 4 == 0);
+  p->wide = a_extent >= 4 && b_extent >= 4;
 }
 
 template <class T, int EPI> void dispatch(const GemmDesc& g, GemmParams p, hipStream_t s) {
@@ -382,7 +414,7 @@ template <class T, int EPI> void dispatch(const GemmDesc& g, GemmParams p, hipSt
 GemmParams base_params(const GemmDesc& g) {
   GemmParams p;
   p.A = g.A; p.B = g.B; p.C = nullptr; p.bias = nullptr; p.part = nullptr; p.aux = nullptr;
-  p.I = g.I; p.J = g.J; p.R = g.R; p.lda = g.lda; p.ldb = g.ldb; p.a_vec = 0; p.b_vec = 0;
+  p.I = g.I; p.J = g.J; p.R = g.R; p.lda = g.lda; p.ldb = g.ldb; p.a_vec = 0; p.b_vec = 0; p.wide = 0;
   return p;
 }
 
