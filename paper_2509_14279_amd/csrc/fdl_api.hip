@@ -118,7 +118,7 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   // Large batches on the tuned kernel (tile-aligned N and K): the weights are transposed first, 4 N K bytes of traffic
   // against about 6 % of the contraction's time; that pays from roughly 10^4 rows, with a margin for the extra launch.
   q.fwd_bytes_plain = off;
-  q.f1_wt = q.f1_fast && !q.pad && M >= 32768;
+  q.f1_wt = q.f1_fast && !q.pad && M >= kTransposeFromRows;
   q.off_wt = off; off += align256(q.f1_wt ? (size_t)N * K * 2 : 0);
   q.fwd_bytes = off;
 
@@ -518,8 +518,9 @@ namespace {
 // partials of db, the fp32 partial sums of a split dW reduction, and the padded copy of X's last rows.
 struct ReluPlan {
   int f1_fast, b3_fast, b4_fast, b4_split, f1_wb, b3_wb, b4_wb;
+  int f1_wt;               // the forward product (and its recomputation) reads the weights from a transposed copy
   int64_t b4_fast_rows;
-  size_t off_g, off_colpart, off_dwpart, off_xtail, bytes;
+  size_t off_g, off_colpart, off_dwpart, off_xtail, off_wt, bytes;
 };
 bool make_relu_plan(int dt, int64_t M, int64_t K, int64_t N, ReluPlan* q) {
   if (dt != kF32 && dt != kBF16) return false;
@@ -540,6 +541,8 @@ bool make_relu_plan(int dt, int64_t M, int64_t K, int64_t N, ReluPlan* q) {
   q->off_colpart = off; off += align256((size_t)colsum_groups(Mp) * N * cs);
   q->off_dwpart = off; off += align256(b4_parts > 1 ? (size_t)b4_parts * N * K * 4 : 0);
   q->off_xtail = off; off += align256(q->f1_fast ? fast_f1_tail_bytes(M, K) : 0);
+  q->f1_wt = q->f1_fast && M >= kTransposeFromRows;
+  q->off_wt = off; off += align256(q->f1_wt ? (size_t)N * K * 2 : 0);
   q->bytes = off;
   return true;
 }
@@ -571,7 +574,9 @@ extern "C" fdl_status fdl_linear_relu_forward(fdl_dtype dt, int64_t M, int64_t K
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   char* ws = static_cast<char*>(workspace);
   if (q.f1_fast) {
-    launch_fast_xwt(1, M, K, N, X, false, W, b, nullptr, Y, ws + q.off_xtail, s);
+    void* Wt = q.f1_wt ? ws + q.off_wt : nullptr;
+    if (q.f1_wt) launch_fast_transpose(N, K, W, Wt, s);
+    launch_fast_xwt(1, M, K, N, X, false, W, Wt, b, nullptr, Y, ws + q.off_xtail, s);
   } else {
     GemmDesc g = {X, W, M, N, K, K, K, true, true, q.f1_wb};
     launch_generic_xwt((int)dt, 1, g, b, nullptr, Y, s);
@@ -606,7 +611,9 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
   void* colpart = ws + q.off_colpart;
   // G = dY where X W^T + b > 0: the pre-activation is recomputed and never stored
   if (p.f1_fast) {
-    launch_fast_xwt(2, M, K, N, X, false, W, b, dY, G, ws + q.off_xtail, s);
+    void* Wt = p.f1_wt ? ws + q.off_wt : nullptr;
+    if (p.f1_wt) launch_fast_transpose(N, K, W, Wt, s);
+    launch_fast_xwt(2, M, K, N, X, false, W, Wt, b, dY, G, ws + q.off_xtail, s);
   } else {
     GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
     launch_generic_xwt((int)dt, 2, g, b, dY, G, s);
@@ -678,7 +685,8 @@ namespace {
 struct FfnPlan {
   int gate_fused;          // 1: one kernel forms both products and the gated activation (no M x H round trip)
   int up_fast, down_fast, up_wb, down_wb;
-  size_t off_g, off_u, off_xtail, bytes;
+  int down_wt;             // the down projection reads its weights from a transposed copy
+  size_t off_g, off_u, off_xtail, off_wt, bytes;
 };
 bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   if (dt != kF32 && dt != kBF16) return false;
@@ -697,6 +705,8 @@ bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   q->off_g = off; off += mh;
   q->off_u = off; off += q->gate_fused ? 0 : mh;    // the fused kernel never materialises the up product
   q->off_xtail = off; off += align256((q->up_fast || q->gate_fused) ? fast_f1_tail_bytes(M, D) : 0);
+  q->down_wt = q->down_fast && M >= kTransposeFromRows;
+  q->off_wt = off; off += align256(q->down_wt ? (size_t)D * H * 2 : 0);
   q->bytes = off;
   return true;
 }
@@ -727,8 +737,8 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   if (q.gate_fused) {
     launch_fast_gate(M, D, H, X, Wg, Wu, G, ws + q.off_xtail, s);
   } else if (q.up_fast) {
-    launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, G, ws + q.off_xtail, s);
-    launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, U, ws + q.off_xtail, s);
+    launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, nullptr, G, ws + q.off_xtail, s);
+    launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, nullptr, U, ws + q.off_xtail, s);
   } else {
     GemmDesc g = {X, Wg, M, H, D, D, D, true, true, q.up_wb};
     launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, G, s);
@@ -737,7 +747,9 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   }
   if (!q.gate_fused) launch_silu_mul((int)dt, M * H, G, U, G, s);
   if (q.down_fast) {
-    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, nullptr, nullptr, Y, nullptr, s);
+    void* Wt = q.down_wt ? ws + q.off_wt : nullptr;
+    if (q.down_wt) launch_fast_transpose(D, H, Wd, Wt, s);
+    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, Wt, nullptr, nullptr, Y, nullptr, s);
   } else {
     GemmDesc g = {G, Wd, M, D, H, H, H, true, true, q.down_wb};
     launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, Y, s);

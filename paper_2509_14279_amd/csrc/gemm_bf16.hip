@@ -919,9 +919,9 @@ void launch_fast_f1_padded(int64_t M, int64_t K, int64_t N, const void* X, const
 //   kind 0: plain product (bias may be null: then none is added)      kind 1: max(. , 0)
 //   kind 2: aux[m][n] where the sum is positive, else 0
 // xtail: fast_f1_tail_bytes(M, K) bytes of scratch when M is not a multiple of 256, unless X itself has readable rows
-// up to the next multiple of 256 (x_padded).
+// up to the next multiple of 256 (x_padded).  Wt: null, or W^T [K][N] from launch_fast_transpose.
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
-                     const float* bias, const void* aux, void* out, void* xtail, hipStream_t s) {
+                     const void* Wt, const float* bias, const void* aux, void* out, void* xtail, hipStream_t s) {
   FastParams p = {};
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)X; p.ldp = K; p.ldq = K;
   p.C = (bf16_t*)out; p.bias = bias; p.aux = (const bf16_t*)aux;
@@ -932,6 +932,21 @@ void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, b
     p.Qtail = (const bf16_t*)xtail;
     hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, K,
                        (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail, kTile);
+  }
+  if (Wt != nullptr) {   // the weights as the r-major operand (see launch_fast_f1)
+    p.P = (const bf16_t*)Wt; p.ldp = N; p.nkt = (int)(K / kB3BK);
+    constexpr int NST = stages_of(kB3BK);
+#define FDL_XWT_T(EPI)                                                            \
+  do {                                                                            \
+    if (rag) launch<true, false, EPI, kB3BK, NST, true>(p, s);                    \
+    else launch<true, false, EPI, kB3BK, NST, false>(p, s);                       \
+  } while (0)
+    if (kind == 1) FDL_XWT_T(EPI_RELU);
+    else if (kind == 2) FDL_XWT_T(EPI_MASK);
+    else if (bias != nullptr) FDL_XWT_T(EPI_BIAS);
+    else FDL_XWT_T(EPI_STORE);
+#undef FDL_XWT_T
+    return;
   }
   constexpr int NS = stages_of(kF1BK);
 #define FDL_XWT(EPI)                                                              \

@@ -168,9 +168,11 @@ void launch_fast_f1_padded(int64_t M, int64_t K, int64_t N, const void* X, const
 void launch_fast_b3_padded(int64_t M, int64_t K, int64_t N, const void* dZ, const void* Wp, void* dX, hipStream_t s);
 void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const void* dZ, const void* X, void* dwpart,
                            hipStream_t s);
-// sibling operators on the forward product's kernel (see gemm_bf16.hip); shapes as fast_f1_supported
+// sibling operators on the forward product's kernel (see gemm_bf16.hip); shapes as fast_f1_supported;
+// Wt: null, or the transposed weights from launch_fast_transpose
+constexpr int64_t kTransposeFromRows = 32768;   // batch size from which transposing the weights first pays
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
-                     const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
+                     const void* Wt, const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
 // gate and up products of the feed-forward block with the gated activation in the epilogue (see gemm_bf16.hip)
 bool fast_gate_supported(int64_t M, int64_t D, int64_t H);
 void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, void* Hout,

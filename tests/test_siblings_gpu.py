@@ -82,7 +82,9 @@ def relu_mask_slack(n, ref_b, acc_unit):
     return {"dX": Gamb @ np.abs(n["W"]), "dW": Gamb.T @ np.abs(n["X"]), "db": Gamb.sum(axis=0)}, int(amb.sum())
 
 
-@pytest.mark.parametrize("dtype,M,K,N", BLOCK_SHAPES + [("bf16", 1000, 256, 768), ("bf16", 4096, 512, 1024)])
+# (the last two: batches from 32768 rows, where the forward product and its recomputation read transposed weights)
+@pytest.mark.parametrize("dtype,M,K,N", BLOCK_SHAPES + [("bf16", 1000, 256, 768), ("bf16", 4096, 512, 1024),
+                                                       ("bf16", 32768, 128, 256), ("bf16", 32805, 256, 512)])
 def test_linear_relu_forward_and_backward(dtype, M, K, N):
     cfg = I.custom(dtype, M, K, N, seed=6500 + M + K + N)
     t = I.generate(cfg)
@@ -197,7 +199,8 @@ def test_norms_constant_and_zero_rows():
 # the tuned kernel (D a multiple of 256) or the generic one (384); generic kernels throughout (unaligned D or H); fp32
 FFN_SHAPES = [("bf16", 512, 512, 1024), ("bf16", 300, 256, 768), ("bf16", 1024, 1024, 2816), ("bf16", 130, 100, 200),
               ("bf16", 256, 128, 128), ("bf16", 640, 384, 384), ("bf16", 2049, 256, 1152),
-              ("bf16", 64, 256, 264), ("f32", 130, 70, 200), ("f32", 33, 64, 128), ("f32", 1, 1, 1), ("bf16", 3, 5, 7)]
+              ("bf16", 64, 256, 264), ("f32", 130, 70, 200), ("f32", 33, 64, 128), ("f32", 1, 1, 1), ("bf16", 3, 5, 7),
+              ("bf16", 32800, 256, 384)]     # a batch large enough for the down projection's transposed weights
 
 
 @pytest.mark.parametrize("dtype,M,D,Hd", FFN_SHAPES)
