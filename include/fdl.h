@@ -145,7 +145,7 @@ FDL_API fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N,
  * Forward pass for inference (the paper's experiments are mostly forward kernels: section "Optimizing individual
  * operations", task table of the robust kernel benchmark): Y as fdl_forward computes it, and nothing saved for a
  * backward pass.  The pre-activation passes through Y itself and is normalised in place, so the workspace holds no
- * M x N tensor: row statistics, partial statistics where the contraction emits them, and for batches of 32768 rows
+ * M x N tensor: row statistics, partial statistics where the contraction emits them, and for batches of 16384 rows
  * and more on the tuned bf16 kernels a transposed copy of W (2 N K bytes):
  * fdl_forward_inference_workspace_bytes bytes (0 for an invalid dtype or shape), 256-byte aligned.
  * in : X [M,K], W [N,K] (dt);  b, gamma, beta [N] fp32;  eps >= 0.     out: Y [M,N] (dt).

@@ -170,7 +170,7 @@ void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const voi
                            hipStream_t s);
 // sibling operators on the forward product's kernel (see gemm_bf16.hip); shapes as fast_f1_supported;
 // Wt: null, or the transposed weights from launch_fast_transpose
-constexpr int64_t kTransposeFromRows = 32768;   // batch size from which transposing the weights first pays
+constexpr int64_t kTransposeFromRows = 16384;   // batch size from which transposing the weights first pays
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
                      const void* Wt, const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
 // gate and up products of the feed-forward block with the gated activation in the epilogue (see gemm_bf16.hip)

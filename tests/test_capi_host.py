@@ -134,9 +134,9 @@ def test_one_hip_runtime_in_the_process():
 def test_sibling_entry_points_reject_bad_arguments_before_any_launch():
     big = 1 << 30
     # forward for inference
-    # row statistics and (from 32768 rows on) the transposed weights: nothing of size M x N
+    # row statistics and (from 16384 rows on) the transposed weights: nothing of size M x N
     assert api.fdl_forward_inference_workspace_bytes("bf16", 65536, 2048, 8192) < (1 << 22) + 2 * 2048 * 8192
-    assert api.fdl_forward_inference_workspace_bytes("bf16", 16384, 2048, 8192) < 1 << 22
+    assert api.fdl_forward_inference_workspace_bytes("bf16", 8192, 2048, 8192) < 1 << 22
     assert api.fdl_forward_inference_workspace_bytes(9, 8, 8, 8) == 0
     assert api.fdl_forward_inference_raw("f32", 4, 4, 4, 0, P, P, P, P, 1e-5, P, P, big, None) == api.FDL_ERR_NULL
     assert api.fdl_forward_inference_raw("f32", 4, 4, 4, P, P, P, P, P, 1e-5, 0, P, big, None) == api.FDL_ERR_NULL

@@ -120,9 +120,9 @@ def test_small_and_ragged_shapes(dtype, shape):
     ("bf16", (129, 136, 256)), ("bf16", (128, 128, 264)), ("bf16", (200, 248, 2056)), ("bf16", (256, 384, 8200)),
     ("bf16", (385, 256, 8456)), ("bf16", (1024, 1000, 8)), ("bf16", (2048, 1024, 64)), ("bf16", (640, 128, 1000)),
     ("bf16", (4096, 520, 768)), ("bf16", (1500, 768, 776)),
-    # batches from 32768 rows on the tuned kernel: the forward contraction reads the weights from a transposed copy
+    # batches from 16384 rows on the tuned kernel: the forward contraction reads the weights from a transposed copy
     # (whole row tiles; a partial last one; rows longer than 8192: statistics in that kernel's epilogue)
-    ("bf16", (32768, 128, 256)), ("bf16", (32805, 256, 512)), ("bf16", (32768, 128, 8448)),
+    ("bf16", (16384, 128, 256)), ("bf16", (32805, 256, 512)), ("bf16", (16384, 128, 8448)),
 ])
 def test_aligned_and_long_row_shapes(dtype, shape):
     M, K, N = shape
