@@ -149,6 +149,10 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   q.pair_sa = q.pair_sb = 1;
   q.pair = !q.pad && q.b3_fast && q.b4_fast && q.b4_fast_rows == M && fast_pair_plan(M, K, N, &q.pair_sa, &q.pair_sb);
   if (q.pair) q.b4_split = q.pair_sb;
+  // dZ in 32 x 32 blocks where only the fused row kernel writes it and only the tuned kernels read it (no generic
+  // kernel over the last rows, no padded pitch); the vector path of the row kernel needs N % 8 = 0, which the tiles imply
+  q.dz_blocked = dt == kBF16 && q.b1_fused && !q.pad && q.b3_fast && q.b4_fast && q.b4_fast_rows == M && M % 32 == 0 &&
+                 N % 32 == 0;
   // fp32 partial sums of dW: the parts of a split reduction, one more for the rows the fast kernel leaves to the
   // generic one; in padded mode the fast kernel always writes partials
   int b4_parts = q.b4_split + (q.b4_fast && q.b4_fast_rows < M ? 1 : 0);
@@ -381,7 +385,8 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
   {
     PhaseTimer t(FDL_PHASE_B1, s);
     if (p.b1_fused) {
-      launch_b1_fused((int)dt, M, N, p.ldz, p.b1_groups, p.f2_rows != 0, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+      launch_b1_fused((int)dt, M, N, p.ldz, p.b1_groups, p.f2_rows != 0, p.dz_blocked != 0, dY, Zsave, gamma, mean, rstd, dZ,
+                      colpart, s);
     } else {
       launch_b1a((int)dt, M, N, dY, Zsave, gamma, mean, rstd, c12, s);
       launch_b1b((int)dt, M, N, p.ldz, p.b1_rows_per_group, p.b1_groups, dY, Zsave, gamma, mean, rstd, c12, dZ, colpart, s);
@@ -408,14 +413,15 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
     PhaseTimer t(FDL_PHASE_B3, s);
     if (p.pair) {
       // one launch for both contractions (B4 below only sums the partial sums of dW, where its reduction is split)
-      launch_fast_pair(M, K, N, p.pair_sa, p.pair_sb, dZ, W, X, dX, ws + p.off_dxpart, dW, ws + p.off_dwpart, s);
+      launch_fast_pair(M, K, N, p.pair_sa, p.pair_sb, dZ, p.dz_blocked != 0, W, X, dX, ws + p.off_dxpart, dW,
+                       ws + p.off_dwpart, s);
       if (p.pair_sa > 1) sum_later(0, ws + p.off_dxpart, p.pair_sa, M * K, dX);
     } else if (p.pad) {
       void* Wp = ws + p.off_wpad_b;
       launch_fast_pad_weights(K, N, W, nullptr, Wp, nullptr, s);
       launch_fast_b3_padded(M, K, N, dZ, Wp, dX, s);
     } else if (p.b3_fast) {
-      launch_fast_b3(M, K, N, dZ, W, dX, s);
+      launch_fast_b3(M, K, N, dZ, p.dz_blocked != 0, W, dX, s);
     } else {
       GemmDesc g = {dZ, W, M, K, N, p.ldz, K, true, false, p.b3_wb};
       launch_generic_store((int)dt, g, dX, s);
@@ -447,7 +453,7 @@ extern "C" fdl_status fdl_backward(fdl_dtype dt, int64_t M, int64_t K, int64_t N
       const int64_t Mf = p.b4_fast_rows;
       const int extra = Mf < M ? 1 : 0;
       float* dwpart = reinterpret_cast<float*>(ws + p.off_dwpart);
-      launch_fast_b4(Mf, K, N, p.b4_split, extra, dZ, X, dW, dwpart, s);
+      launch_fast_b4(Mf, K, N, p.b4_split, extra, dZ, p.dz_blocked != 0, X, dW, dwpart, s);
       if (extra) {
         const char* dZt = static_cast<const char*>(dZ) + (size_t)Mf * N * 2;
         const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
@@ -620,7 +626,7 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
   }
   launch_colsum((int)dt, M, N, G, colpart, db, s);
   if (p.b3_fast) {
-    launch_fast_b3(M, K, N, G, W, dX, s);
+    launch_fast_b3(M, K, N, G, false, W, dX, s);
   } else {
     GemmDesc g = {G, W, M, K, N, N, K, true, false, p.b3_wb};
     launch_generic_store((int)dt, g, dX, s);
@@ -629,7 +635,7 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
     const int64_t Mf = p.b4_fast_rows;
     const int extra = Mf < M ? 1 : 0;
     float* dwpart = reinterpret_cast<float*>(ws + q.off_dwpart);
-    launch_fast_b4(Mf, K, N, p.b4_split, extra, G, X, dW, dwpart, s);
+    launch_fast_b4(Mf, K, N, p.b4_split, extra, G, false, X, dW, dwpart, s);
     if (extra) {
       const char* Gt = static_cast<const char*>(G) + (size_t)Mf * N * 2;
       const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;

@@ -82,6 +82,7 @@ struct FastParams {
   int nkt;               // reduction slices per workgroup
   int split;
   int xcds;              // accelerator dies the workgroup ids are dealt over (1: no die-aware tile order)
+  int qblocked;          // 1: Q (the library's own dZ buffer, ldq columns) is stored in blocks of 32 x 32, see Loader
 };
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -110,12 +111,29 @@ template <int N> __device__ __forceinline__ void wait_dma() { asm volatile("s_wa
 template <bool RM, int BK> struct Loader {
   // voff[q]: per-lane byte offset of instruction q (constant over the reduction loop).  kDpw instructions per wave
   // fill this wave's quarter of the operand tile; the only per-slice scalar work is one base pointer.
+  // Blocked operand (BK = 32 only): the matrix [rows][ld] is stored as [rows / 32][ld / 32] blocks of 32 x 32
+  // elements, each block row-major and 2 KB long.  Either orientation then reads long runs: a 256-row slice of 32
+  // reduction columns (r-contiguous use) is 8 whole blocks, a slice of 32 reduction rows by 256 columns (r-major use)
+  // is 8 neighbouring blocks, 16 KB in one piece - where a row-major matrix gives the r-contiguous reader 256 runs of
+  // 64 bytes, half a cache line each, whose other half it asks for again one slice later.  The 16-byte chunk a lane
+  // fetches and the LDS slot it lands in are the same as for a row-major operand; only its address differs.
   static constexpr int kDpw = Geo<BK>::kDpw;
   uint32_t voff[kDpw];
-  __device__ __forceinline__ void init(int lane, int64_t ld) {
+  int blocked;
+  __device__ __forceinline__ void init(int lane, int64_t ld, int blocked_operand = 0) {
+    blocked = (BK == 32) ? blocked_operand : 0;
 #pragma unroll
     for (int q = 0; q < kDpw; q++) {
-      if (RM) {
+      if (BK == 32 && blocked && RM) {
+        // r-row 2q + h of this wave's 8 (all in one block row), chunk c: block c / 4, 16-byte piece c % 4 of its row
+        const int h = lane >> 5, slot = lane & 31;
+        const int c = slot ^ (((2 * q + h) & 3) << 2);
+        voff[q] = (uint32_t)((c >> 2) * 2048 + (2 * q + h) * 64 + (c & 3) * 16);
+      } else if (BK == 32 && blocked) {
+        // row 16q + w of this wave's 64 (two block rows), piece slot ^ swizzle of its 64 bytes in the block
+        const int w = lane >> 2, slot = lane & 3, rr = 16 * q + w;
+        voff[q] = (uint32_t)((int64_t)(rr >> 5) * (ld >> 5) * 2048 + (rr & 31) * 64 + ((slot ^ ((w >> 2) & 3)) * 16));
+      } else if (RM) {
         // instruction q covers r-rows 2q, 2q+1 of this wave's BK/4; lane: r-row 2q + h, h = lane/32, slot lane%32
         const int h = lane >> 5, slot = lane & 31;
         const int c = slot ^ (((2 * q + h) & 3) << 2);
@@ -133,6 +151,7 @@ template <bool RM, int BK> struct Loader {
   }
   // first element this wave fetches of the slice that starts at `base` (block tile origin, first r of the slice)
   __device__ __forceinline__ const bf16_t* wave_base(const bf16_t* base, int64_t ld, int wave) const {
+    if (BK == 32 && blocked) return RM ? base + wave * (BK / 4) * 32 : base + (int64_t)(wave * 2) * (ld >> 5) * 1024;
     return RM ? base + (int64_t)(wave * (BK / 4)) * ld : base + (int64_t)(wave * 64) * ld;
   }
   // wbase: wave_base(...) of the slice; wlds: LDS address of this wave's quarter of the operand tile
@@ -267,13 +286,15 @@ __device__ __forceinline__ void gemm_tile_loop(const FastParams& p, char* smem, 
   auto init_offsets = [&]() {
     int lt = lane;
     asm volatile("" : "+v"(lt));
-    lp.init(lt, p.ldp); lq.init(lt, p.ldq);
+    lp.init(lt, p.ldp); lq.init(lt, p.ldq, p.qblocked);
     fp.init(lt, wi); fq.init(lt, wj);
   };
   init_offsets();   // for the initial fill below; every tile recomputes them
 
   const int64_t pstep = P_RM ? (int64_t)BK * p.ldp : BK;
-  const int64_t qstep = Q_RM ? (int64_t)BK * p.ldq : BK;
+  const bool qblk = BK == 32 && p.qblocked != 0;
+  // (a slice step of an r-major operand is 32 rows = one block row either way: 32 ldq elements)
+  const int64_t qstep = Q_RM ? (int64_t)BK * p.ldq : (qblk ? 1024 : BK);
   // first element this wave fetches of slice 0 of the tile at (i0, j0)
   // EPI_GATE: the 256 rows of a P tile are 64 gate rows, the same 64 up rows, the next 64 gate rows and their up rows
   // (rows of P and P2 from i0/2 on), one quarter per wave: a wave's accumulator blocks a = 0, 1 then hold the gate
@@ -286,6 +307,9 @@ __device__ __forceinline__ void gemm_tile_loop(const FastParams& p, char* smem, 
   };
   auto q_origin = [&](int j0) {
     if (RAG && !Q_RM && p.Qtail != nullptr && j0 == (p.tiles_j - 1) * kTile) return lq.wave_base(p.Qtail + r_begin, p.ldq, wave);
+    if (qblk)   // block (j0 / 32, r_begin / 32), or (r_begin / 32, j0 / 32) for the r-major reader
+      return lq.wave_base(Q_RM ? p.Q + ((r_begin >> 5) * (p.ldq >> 5) + (j0 >> 5)) * 1024
+                               : p.Q + ((int64_t)(j0 >> 5) * (p.ldq >> 5) + (r_begin >> 5)) * 1024, p.ldq, wave);
     return lq.wave_base(Q_RM ? p.Q + r_begin * p.ldq + j0 : p.Q + (int64_t)j0 * p.ldq + r_begin, p.ldq, wave);
   };
 
@@ -986,8 +1010,10 @@ void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void
   }
 }
 
-void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s) {
+void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, bool dz_blocked, const void* W, void* dX,
+                    hipStream_t s) {
   FastParams p = {};
+  p.qblocked = dz_blocked ? 1 : 0;
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = N;
   p.C = (bf16_t*)dX;
   p.I = (int)K; p.J = (int)M; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
@@ -1035,9 +1061,10 @@ int fast_b4_split(int64_t M, int64_t K, int64_t N) {
 // kernel writes fp32 partial sums dwpart[0 .. split); the caller may add `extra` more partials behind them (the
 // rows the fast kernel does not cover) and then sums them (launch_fast_b4_reduce, or the backward pass's finishing
 // launch); otherwise dW is final on return.
-void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, const void* X, void* dW,
-                    void* dwpart, hipStream_t s) {
+void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, bool dz_blocked, const void* X,
+                    void* dW, void* dwpart, hipStream_t s) {
   FastParams p = {};
+  p.qblocked = dz_blocked ? 1 : 0;
   p.P = (const bf16_t*)X; p.Q = (const bf16_t*)dZ; p.ldp = K; p.ldq = N;
   p.C = (bf16_t*)dW; p.Cpart = (float*)dwpart;
   p.I = (int)K; p.J = (int)N; p.tiles_i = (int)(K / kTile); p.tiles_j = (int)(N / kTile);
@@ -1098,9 +1125,10 @@ bool fast_pair_plan(int64_t M, int64_t K, int64_t N, int* sa_out, int* sb_out) {
 
 // dxpart: sa [M][K] fp32 partial sums (sa > 1), dwpart: sb [N][K] (sb > 1); an unsplit product goes to dX / dW directly.
 // The caller sums the partials (launch_fast_b4_reduce works for either).
-void launch_fast_pair(int64_t M, int64_t K, int64_t N, int sa, int sb, const void* dZ, const void* W, const void* X,
-                      void* dX, void* dxpart, void* dW, void* dwpart, hipStream_t s) {
+void launch_fast_pair(int64_t M, int64_t K, int64_t N, int sa, int sb, const void* dZ, bool dz_blocked, const void* W,
+                      const void* X, void* dX, void* dxpart, void* dW, void* dwpart, hipStream_t s) {
   FastParams pa = {}, pb = {};
+  pa.qblocked = pb.qblocked = dz_blocked ? 1 : 0;
   pa.P = (const bf16_t*)W; pa.Q = (const bf16_t*)dZ; pa.ldp = K; pa.ldq = N; pa.C = (bf16_t*)dX; pa.Cpart = (float*)dxpart;
   pa.I = (int)K; pa.J = (int)M; pa.tiles_i = (int)(K / kTile); pa.tiles_j = (int)(M / kTile);
   pa.nkt = (int)(N / kB3BK / sa); pa.split = sa;

@@ -44,6 +44,7 @@ struct Plan {
   int64_t b4_fast_rows;   // rows of the reduction the fast kernel covers (the rest goes through the generic kernel)
   int pair;               // 1: dX and dW share one launch, their reductions split into pair_sa and pair_sb parts
   int pair_sa, pair_sb;
+  int dz_blocked;         // 1: dZ lives in 32 x 32 blocks (fused row kernel -> tuned dX and dW kernels only)
   size_t off_dxpart;      // float [pair_sa][M][K] (pair_sa > 1)
   int pad;                // 1: padded mode of the fast contractions (N, K multiples of 8, not both of 256)
   int64_t ldz;            // pitch of the dZ buffer in elements (N, or N rounded up to 256 in padded mode)
@@ -116,8 +117,9 @@ bool b1_fused_supported(int dt, int64_t N);
 int b1_fused_groups(int dt, int64_t M, int64_t N);   // number of row groups it should be launched with (before capping at M)
 // table: evaluate GELU from the LDS table, as the forward pass did (bf16, plan.f2_rows); else as the other kernels do
 void launch_zero_cols_bf16(void* dZ, int64_t M, int64_t N, int64_t ldz, hipStream_t s);
-void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, const void* dY, const void* Zsave,
-                     const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart,
+// blocked: dZ is written as [M / 32][N / 32] blocks of 32 x 32 elements (bf16, M and N multiples of 32, ldz = N)
+void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, bool blocked, const void* dY,
+                     const void* Zsave, const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart,
                      hipStream_t s);
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
                hipStream_t s);
@@ -178,14 +180,16 @@ bool fast_gate_supported(int64_t M, int64_t D, int64_t H);
 void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, void* Hout,
                       void* xtail, hipStream_t s);
 // dZ must have readable rows up to the next multiple of 256
-void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, const void* W, void* dX, hipStream_t s);
+// dz_blocked: dZ is stored in 32 x 32 blocks (launch_b1_fused with blocked = true; M, N multiples of 32)
+void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, bool dz_blocked, const void* W, void* dX,
+                    hipStream_t s);
 int fast_b4_split(int64_t M, int64_t K, int64_t N);
-void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, const void* X, void* dW,
-                    void* dwpart, hipStream_t s);
+void launch_fast_b4(int64_t M, int64_t K, int64_t N, int split, int extra, const void* dZ, bool dz_blocked, const void* X,
+                    void* dW, void* dwpart, hipStream_t s);
 void launch_fast_b4_reduce(int64_t K, int64_t N, int parts, const void* dwpart, void* dW, hipStream_t s);
 // dX and dW in one launch where together they have at most a tile per compute unit; sa, sb: parts of the two reductions
 bool fast_pair_plan(int64_t M, int64_t K, int64_t N, int* sa, int* sb);
-void launch_fast_pair(int64_t M, int64_t K, int64_t N, int sa, int sb, const void* dZ, const void* W, const void* X,
-                      void* dX, void* dxpart, void* dW, void* dwpart, hipStream_t s);
+void launch_fast_pair(int64_t M, int64_t K, int64_t N, int sa, int sb, const void* dZ, bool dz_blocked, const void* W,
+                      const void* X, void* dX, void* dxpart, void* dW, void* dwpart, hipStream_t s);
 
 }  // namespace fdl

@@ -377,7 +377,13 @@ template <class T, int V> __device__ __forceinline__ typename RawVec<T, V>::type
 // and the hardware exponential.  The backward pass must evaluate GELU exactly as the forward pass that produced
 // mean and rstd did - for a constant row, rstd = eps^-1/2 multiplies any difference between the two into Ahat -
 // so the launcher selects TAB if and only if the forward pass normalised with the table.
-template <class T, int V, int S, int NT, bool TAB>
+// BLK (16-byte vectors, one strip): dZ is written as [M / 32][N / 32] blocks of 32 x 32 elements, each block row-major
+// (what the tuned dX and dW kernels read best, see gemm_bf16.hip).  A row's 16 bytes per lane are then 64-byte pieces,
+// each half of a 128-byte line whose other half belongs to the next row: the group walks rows in neighbouring pairs,
+// parks both rows' vectors in a per-wave LDS area and stores whole lines (lanes 8j .. 8j+3 the even row's piece j,
+// lanes 8j+4 .. 8j+7 the odd row's).  Half-line stores straight from the registers cost the phase a third of its
+// bandwidth (0.55 -> 0.73 ms on 65536 x 8192), halves merged in the L2 still a tenth.
+template <class T, int V, int S, int NT, bool TAB, bool BLK = false>
 __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int64_t ldz, const T* __restrict__ dY,
                                                        const T* __restrict__ Z, const float* __restrict__ gamma,
                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
@@ -387,8 +393,11 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int6
   typedef typename RawVec<T, V>::type raw_t;
   typedef GaussTable<true> GT;
   typedef __attribute__((address_space(3))) f32x2 lds_f32x2;
+  static_assert(!BLK || (V * sizeof(T) == 16 && S == 1), "blocked output: 16-byte vectors, one strip");
+  constexpr bool blocked = BLK;
   __shared__ C red[2][NT / 64][2];
   __shared__ __attribute__((aligned(8))) float gtab[TAB ? 2 * GT::kEntries : 2];
+  __shared__ __attribute__((aligned(16))) raw_t park[BLK ? NT / 64 : 1][2][BLK ? 64 : 1];   // [wave][row of the pair][lane]
   uint32_t gorg = 0;
   if (TAB) {
     GT::build(gtab, threadIdx.x, NT);
@@ -424,8 +433,13 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int6
   for (int buf = 0; buf < 2; buf++)
 #pragma unroll
     for (int s = 0; s < S; s++) { bdy[buf][s] = raw_zero<T, V>(); bz[buf][s] = raw_zero<T, V>(); }
-  fetch(0, blockIdx.x);
-  fetch(1, blockIdx.x + G);
+  // Row-major dZ: the group walks rows b, b + G, b + 2G, ... .  Blocked dZ: rows 2b, 2b + 1, then 2G further on - the
+  // two rows in flight are neighbours, so the two 64-byte halves of every line of dZ leave the same compute unit
+  // within one row time and merge in its L2 (M is even where dZ is blocked).
+  const int64_t first = blocked ? 2 * (int64_t)blockIdx.x : (int64_t)blockIdx.x;
+  const int64_t second = blocked ? 1 : G;
+  fetch(0, first);
+  fetch(1, first + second);
 
   const C inv_n = (C)1 / (C)N;
   auto process = [&](int buf, int64_t row) {
@@ -468,16 +482,35 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int6
         dz[v] = (g[s][v] - c1 - ah[s][v] * c2) * gp[s][v];
         accz[s][v] += dz[v];
       }
-      if (ok[s]) {
-        typename RawVec<T, V>::type o;
-        if constexpr (V == 1) o = to_storage<T, C>(dz[0]); else { for (int v = 0; v < V; v++) o[v] = to_storage<T, C>(dz[v]); }
+      typename RawVec<T, V>::type o;
+      if constexpr (V == 1) o = to_storage<T, C>(dz[0]); else { for (int v = 0; v < V; v++) o[v] = to_storage<T, C>(dz[v]); }
+      if constexpr (BLK) {
+        // (every lane takes part in the stores, also one whose own columns lie past the end of the row: the pieces it
+        //  stores belong to other lanes' columns)
+        const int wv = threadIdx.x >> 6, ln = threadIdx.x & 63;
+        if (ok[s]) park[wv][buf][ln] = o;
+        if (buf == 1) {
+          // this wave's 16 pieces per row (piece = 4 lanes = 32 columns = one block): two stores of 8 whole lines
+          const int64_t even = row - 1;
+#pragma unroll
+          for (int half = 0; half < 2; half++) {
+            const int j = half * 8 + (ln >> 3), i = ln & 7;
+            const int64_t nb = (int64_t)wv * 16 + j;                       // block column of piece j
+            if (nb * 32 < N) {                                             // N is a multiple of 32: a piece is whole or absent
+              const raw_t v = park[wv][i >> 2][4 * j + (i & 3)];
+              const int64_t at = (((even >> 5) * (N >> 5) + nb) << 10) + ((even & 31) << 5) + i * 8;
+              __builtin_nontemporal_store(v, reinterpret_cast<raw_t*>(dZ + at));
+            }
+          }
+        }
+      } else if (ok[s]) {
         __builtin_nontemporal_store(o, reinterpret_cast<typename RawVec<T, V>::type*>(dZ + row * ldz + col[s]));
       }
     }
   };
-  for (int64_t row = blockIdx.x; row < M; row += 2 * G) {
+  for (int64_t row = first; row < M; row += 2 * G) {
     process(0, row);
-    if (row + G < M) process(1, row + G);
+    if (row + second < M) process(1, row + second);
   }
 #pragma unroll
   for (int s = 0; s < S; s++)
@@ -725,7 +758,7 @@ inline bool fused_shape(int64_t N, int V, bool vec, FusedShape* out) {
   return false;
 }
 
-template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int64_t ldz, int groups, const void* dY, const void* Z,
+template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int64_t ldz, int groups, bool blocked, const void* dY, const void* Z,
                                                 const float* gamma, const float* mean, const float* rstd, void* dZ,
                                                 void* colpart, hipStream_t s) {
   typedef typename ComputeOf<T>::type C;
@@ -736,12 +769,20 @@ template <class T, bool TAB> void b1_fused_impl(int64_t M, int64_t N, int64_t ld
 #define FDL_B1F(VV, SS, NTT)                                                                                       \
   hipLaunchKernelGGL((b1_fused_kernel<T, VV, SS, NTT, TAB>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N, ldz,      \
                      (const T*)dY, (const T*)Z, gamma, mean, rstd, (T*)dZ, (C*)colpart)
-  if (V == VMAX) {
+#define FDL_B1F_BLK(NTT)                                                                                           \
+  hipLaunchKernelGGL((b1_fused_kernel<T, VMAX, 1, NTT, TAB, true>), dim3((unsigned)groups), dim3(NTT), 0, s, M, N,  \
+                     ldz, (const T*)dY, (const T*)Z, gamma, mean, rstd, (T*)dZ, (C*)colpart)
+  if (V == VMAX && blocked) {
+    if constexpr (sizeof(T) == 2) {
+      if (fs.nt == 256) FDL_B1F_BLK(256); else if (fs.nt == 512) FDL_B1F_BLK(512); else FDL_B1F_BLK(1024);
+    }
+  } else if (V == VMAX) {
     if (fs.nt == 256) FDL_B1F(VMAX, 1, 256); else if (fs.nt == 512) FDL_B1F(VMAX, 1, 512); else FDL_B1F(VMAX, 1, 1024);
   } else {
     if (fs.s == 2) FDL_B1F(1, 2, 1024);
     else if (fs.nt == 256) FDL_B1F(1, 1, 256); else if (fs.nt == 512) FDL_B1F(1, 1, 512); else FDL_B1F(1, 1, 1024);
   }
+#undef FDL_B1F_BLK
 #undef FDL_B1F
 }
 
@@ -928,11 +969,13 @@ int b1_fused_groups(int dt, int64_t M, int64_t N) {
   return (int)groups;
 }
 
-void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, const void* dY, const void* Zsave,
-                     const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart, hipStream_t s) {
-  if (dt == kF32) b1_fused_impl<float, false>(M, N, ldz, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
-  else if (table) b1_fused_impl<bf16_t, true>(M, N, ldz, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
-  else b1_fused_impl<bf16_t, false>(M, N, ldz, groups, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+void launch_b1_fused(int dt, int64_t M, int64_t N, int64_t ldz, int groups, bool table, bool blocked, const void* dY,
+                     const void* Zsave, const float* gamma, const float* mean, const float* rstd, void* dZ, void* colpart,
+                     hipStream_t s) {
+  const bool blk = blocked && dt == kBF16;
+  if (dt == kF32) b1_fused_impl<float, false>(M, N, ldz, groups, false, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else if (table) b1_fused_impl<bf16_t, true>(M, N, ldz, groups, blk, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
+  else b1_fused_impl<bf16_t, false>(M, N, ldz, groups, blk, dY, Zsave, gamma, mean, rstd, dZ, colpart, s);
 }
 
 void launch_b2(int dt, int64_t N, int groups, const void* colpart, float* dbeta, float* dgamma, float* db,
