@@ -151,8 +151,10 @@ bool make_plan(int dt, int64_t M, int64_t K, int64_t N, Plan* p) {
   if (q.pair) q.b4_split = q.pair_sb;
   // dZ in 32 x 32 blocks where only the fused row kernel writes it and only the tuned kernels read it (no generic
   // kernel over the last rows, no padded pitch); the vector path of the row kernel needs N % 8 = 0, which the tiles imply
+  // (the row kernel pays for it with about 8 % of its time where a row fills 1024 threads, dX gains about 9 %: not
+  //  worth it when such rows meet a short K)
   q.dz_blocked = dt == kBF16 && q.b1_fused && !q.pad && q.b3_fast && q.b4_fast && q.b4_fast_rows == M && M % 32 == 0 &&
-                 N % 32 == 0;
+                 N % 32 == 0 && (K >= 1024 || N <= 4096);
   // fp32 partial sums of dW: the parts of a split reduction, one more for the rows the fast kernel leaves to the
   // generic one; in padded mode the fast kernel always writes partials
   int b4_parts = q.b4_split + (q.b4_fast && q.b4_fast_rows < M ? 1 : 0);

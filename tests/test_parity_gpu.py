@@ -123,6 +123,9 @@ def test_small_and_ragged_shapes(dtype, shape):
     # batches from 16384 rows on the tuned kernel: the forward contraction reads the weights from a transposed copy
     # (whole row tiles; a partial last one; rows longer than 8192: statistics in that kernel's epilogue)
     ("bf16", (16384, 128, 256)), ("bf16", (32805, 256, 512)), ("bf16", (16384, 128, 8448)),
+    # dZ in 32 x 32 blocks (fused row kernel + tuned dX and dW over all rows; with rows of 1024 threads only from
+    # K = 1024): whole and partial wavefronts at the end of a row, split dW, paired dX + dW launch
+    ("bf16", (256, 1024, 4352)), ("bf16", (384, 1024, 7936)), ("bf16", (512, 1024, 8192)), ("bf16", (1024, 256, 2304)),
 ])
 def test_aligned_and_long_row_shapes(dtype, shape):
     M, K, N = shape
