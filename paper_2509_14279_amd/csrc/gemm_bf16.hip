@@ -7,11 +7,13 @@
 // the forward pass takes them here) is a sum inside the lane plus one cross-half exchange.
 //
 //   F1  Z[m][n]  = sum_k X[m][k] W[n][k] + b[n]   P = W (i = n, r-contiguous)   Q = X  (j = m, r-contiguous)
+//       or, for large batches,                    P = W^T (a transposed copy: r = k major)
 //       (also the forward product of the sibling operators: Linear+ReLU, its backward pass's recomputation of the
 //        pre-activation with the activation mask applied to the upstream gradient, and the three products of the
 //        gated feed-forward block)
 //   B3  dX[m][k] = sum_n dZ[m][n] W[n][k]         P = W (i = k, r = n major)    Q = dZ (j = m, r-contiguous)
 //   B4  dW[n][k] = sum_m dZ[m][n] X[m][k]         P = X (i = k, r = m major)    Q = dZ (j = n, r = m major)
+//       (dZ is the library's own buffer and may be stored in 32 x 32 blocks, which suits both of its readers: Loader)
 // (the linear layer's forward, grad-input and grad-weight products of the paper's linear tasks.)
 //
 // Workgroup: 256 threads = 4 waves (2 x 2), one per SIMD; block tile 256 x 256, wave tile 128 x 128 as 4 x 4

@@ -417,8 +417,9 @@ __global__ __launch_bounds__(NT) void b1_fused_kernel(int64_t M, int64_t N, int6
       accb[s][v] = 0; accg[s][v] = 0; accz[s][v] = 0;
     }
   }
-  // Two rows are kept in flight: buffers 0 and 1 hold the raw rows r and r + G (G = gridDim.x); as soon as a
-  // buffer has been unpacked its refill with row r + 2G is issued, ahead of that row's barrier and second phase.
+  // Two rows are kept in flight: buffers 0 and 1 hold the raw rows r and r + G (G = gridDim.x; r and r + 1 where dZ
+  // is blocked); as soon as a buffer has been unpacked its refill with the row 2G further on is issued, ahead of that
+  // row's barrier and second phase.
   raw_t bdy[2][S], bz[2][S];
   const int64_t G = gridDim.x;
   auto fetch = [&](int buf, int64_t r) {
