@@ -694,7 +694,8 @@ struct FfnPlan {
   int gate_fused;          // 1: one kernel forms both products and the gated activation (no M x H round trip)
   int up_fast, down_fast, up_wb, down_wb;
   int down_wt;             // the down projection reads its weights from a transposed copy
-  size_t off_g, off_u, off_xtail, off_wt, bytes;
+  int gate_wt;             // the fused gate/up kernel reads both weight matrices from one interleaved transposed copy
+  size_t off_g, off_u, off_xtail, off_wt, off_wcat, bytes;
 };
 bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   if (dt != kF32 && dt != kBF16) return false;
@@ -715,6 +716,8 @@ bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   q->off_xtail = off; off += align256((q->up_fast || q->gate_fused) ? fast_f1_tail_bytes(M, D) : 0);
   q->down_wt = q->down_fast && M >= kTransposeFromRows;
   q->off_wt = off; off += align256(q->down_wt ? (size_t)D * H * 2 : 0);
+  q->gate_wt = q->gate_fused && M >= kTransposeFromRows && H % 64 == 0 && D % 64 == 0;
+  q->off_wcat = off; off += align256(q->gate_wt ? (size_t)2 * D * H * 2 : 0);
   q->bytes = off;
   return true;
 }
@@ -743,7 +746,9 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   void* G = ws + q.off_g;
   void* U = ws + q.off_u;
   if (q.gate_fused) {
-    launch_fast_gate(M, D, H, X, Wg, Wu, G, ws + q.off_xtail, s);
+    void* Wcat = q.gate_wt ? ws + q.off_wcat : nullptr;
+    if (q.gate_wt) launch_fast_transpose_gate(H, D, Wg, Wu, Wcat, s);
+    launch_fast_gate(M, D, H, X, Wg, Wu, Wcat, G, ws + q.off_xtail, s);
   } else if (q.up_fast) {
     launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, nullptr, G, ws + q.off_xtail, s);
     launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, nullptr, U, ws + q.off_xtail, s);

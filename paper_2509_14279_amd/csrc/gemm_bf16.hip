@@ -303,7 +303,7 @@ __device__ __forceinline__ void gemm_tile_loop(const FastParams& p, char* smem, 
   // product and a = 2, 3 the up product of the same 64 output columns, register for register, and the gated
   // activation needs no exchange between lanes.  The tile is 128 output columns wide.
   auto p_origin = [&](int i0) {
-    if (EPI == EPI_GATE)
+    if (EPI == EPI_GATE && !P_RM)   // (an r-major P for this epilogue is one matrix with that row order built in)
       return ((wave & 1) ? p.P2 : p.P) + (int64_t)((i0 >> 1) + (wave >> 1) * 64) * p.ldp + r_begin;
     return lp.wave_base(P_RM ? p.P + r_begin * p.ldp + i0 : p.P + (int64_t)i0 * p.ldp + r_begin, p.ldp, wave);
   };
@@ -730,8 +730,11 @@ __global__ __launch_bounds__(256) void reduce_split_kernel(const float* __restri
 
 // dst [cols][rows] = src [rows][cols]^T in 64 x 64 tiles through LDS (rows, cols multiples of 64): both sides move
 // 128-byte row segments.
+// The tile of source rows r0 .. r0 + 63 lands in destination columns (r0 / 64) * tile_stride + col_off .. + 63 of a
+// destination with pitch dst_ld (plain transposition: dst_ld = rows, tile_stride = 64, col_off = 0).
 __global__ __launch_bounds__(256) void transpose64_kernel(const bf16_t* __restrict__ src, int64_t rows, int64_t cols,
-                                                          bf16_t* __restrict__ dst) {
+                                                          bf16_t* __restrict__ dst, int64_t dst_ld, int tile_stride,
+                                                          int col_off) {
   __shared__ unsigned short tile[64][66];
   const int64_t c0 = (int64_t)blockIdx.x * 64, r0 = (int64_t)blockIdx.y * 64;
   const int t = threadIdx.x, r = t >> 2, q = (t & 3) * 16;
@@ -749,7 +752,7 @@ __global__ __launch_bounds__(256) void transpose64_kernel(const bf16_t* __restri
     o0[e] = (uint32_t)tile[q + 2 * e][r] | ((uint32_t)tile[q + 2 * e + 1][r] << 16);
     o1[e] = (uint32_t)tile[q + 8 + 2 * e][r] | ((uint32_t)tile[q + 8 + 2 * e + 1][r] << 16);
   }
-  unsigned short* dp = reinterpret_cast<unsigned short*>(dst) + (c0 + r) * rows + r0 + q;
+  unsigned short* dp = reinterpret_cast<unsigned short*>(dst) + (c0 + r) * dst_ld + (r0 / 64) * tile_stride + col_off + q;
   *reinterpret_cast<u32x4*>(dp) = o0;
   *reinterpret_cast<u32x4*>(dp + 8) = o1;
 }
@@ -880,7 +883,16 @@ void launch_fast_pad_weights(int64_t K, int64_t N, const void* W, const float* b
 // Wt [K][N] = W^T (N, K multiples of 64).
 void launch_fast_transpose(int64_t N, int64_t K, const void* W, void* Wt, hipStream_t s) {
   const dim3 grid((unsigned)(K / 64), (unsigned)(N / 64));
-  hipLaunchKernelGGL(transpose64_kernel, grid, dim3(256), 0, s, (const bf16_t*)W, N, K, (bf16_t*)Wt);
+  hipLaunchKernelGGL(transpose64_kernel, grid, dim3(256), 0, s, (const bf16_t*)W, N, K, (bf16_t*)Wt, N, 64, 0);
+}
+
+// Wcat [D][2H]: the transposed gate and up weights side by side in groups of 64 columns - 64 of Wg^T, the same 64 of
+// Wu^T, the next 64 of Wg^T, ... - which is the order in which the gated kernel wants the 256 rows of its P tile
+// (H, D multiples of 64).
+void launch_fast_transpose_gate(int64_t H, int64_t D, const void* Wg, const void* Wu, void* Wcat, hipStream_t s) {
+  const dim3 grid((unsigned)(D / 64), (unsigned)(H / 64));
+  hipLaunchKernelGGL(transpose64_kernel, grid, dim3(256), 0, s, (const bf16_t*)Wg, H, D, (bf16_t*)Wcat, 2 * H, 128, 0);
+  hipLaunchKernelGGL(transpose64_kernel, grid, dim3(256), 0, s, (const bf16_t*)Wu, H, D, (bf16_t*)Wcat, 2 * H, 128, 64);
 }
 
 // part != nullptr: also emit the per-(row, 128-column tile) partial statistics of GELU(Zsave).
@@ -994,22 +1006,29 @@ bool fast_gate_supported(int64_t M, int64_t D, int64_t H) {
   return M >= kMinRaggedRows && H > 0 && H % 128 == 0 && D > 0 && D % (stages_of(kF1BK) * kF1BK) == 0 && H <= (1 << 24) &&
          M <= (1 << 24) && (H / 128) * tj <= (1 << 30);
 }
-void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, void* Hout,
-                      void* xtail, hipStream_t s) {
+void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, const void* Wcat,
+                      void* Hout, void* xtail, hipStream_t s) {
   FastParams p = {};
   p.P = (const bf16_t*)Wg; p.P2 = (const bf16_t*)Wu; p.Q = (const bf16_t*)X; p.ldp = D; p.ldq = D;
   p.C = (bf16_t*)Hout;
   p.I = (int)H; p.J = (int)M; p.tiles_i = (int)(H / 128); p.tiles_j = (int)((M + kTile - 1) / kTile);
   p.nkt = (int)(D / kF1BK); p.split = 1;
-  constexpr int NS = stages_of(kF1BK);
-  if (M % kTile) {
+  const bool rag = M % kTile != 0;
+  if (rag) {
     p.Qtail = (const bf16_t*)xtail;
     hipLaunchKernelGGL(copy_tail_rows_kernel, dim3(64), dim3(256), 0, s, (const bf16_t*)X, M, D,
                        (int64_t)(p.tiles_j - 1) * kTile, (bf16_t*)xtail, kTile);
-    launch<false, false, EPI_GATE, kF1BK, NS, true>(p, s);
-  } else {
-    launch<false, false, EPI_GATE, kF1BK, NS, false>(p, s);
   }
+  if (Wcat != nullptr) {   // Wcat from launch_fast_transpose_gate: the weights as one r-major operand (see launch_fast_f1)
+    p.P = (const bf16_t*)Wcat; p.P2 = nullptr; p.ldp = 2 * H; p.nkt = (int)(D / kB3BK);
+    constexpr int NST = stages_of(kB3BK);
+    if (rag) launch<true, false, EPI_GATE, kB3BK, NST, true>(p, s);
+    else launch<true, false, EPI_GATE, kB3BK, NST, false>(p, s);
+    return;
+  }
+  constexpr int NS = stages_of(kF1BK);
+  if (rag) launch<false, false, EPI_GATE, kF1BK, NS, true>(p, s);
+  else launch<false, false, EPI_GATE, kF1BK, NS, false>(p, s);
 }
 
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, bool dz_blocked, const void* W, void* dX,

@@ -177,8 +177,10 @@ void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, b
                      const void* Wt, const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
 // gate and up products of the feed-forward block with the gated activation in the epilogue (see gemm_bf16.hip)
 bool fast_gate_supported(int64_t M, int64_t D, int64_t H);
-void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, void* Hout,
-                      void* xtail, hipStream_t s);
+// Wcat: null, or the interleaved transposed weights [D][2H] from launch_fast_transpose_gate
+void launch_fast_transpose_gate(int64_t H, int64_t D, const void* Wg, const void* Wu, void* Wcat, hipStream_t s);
+void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, const void* Wcat,
+                      void* Hout, void* xtail, hipStream_t s);
 // dZ must have readable rows up to the next multiple of 256
 // dz_blocked: dZ is stored in 32 x 32 blocks (launch_b1_fused with blocked = true; M, N multiples of 32)
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, bool dz_blocked, const void* W, void* dX,

@@ -200,7 +200,7 @@ def test_norms_constant_and_zero_rows():
 FFN_SHAPES = [("bf16", 512, 512, 1024), ("bf16", 300, 256, 768), ("bf16", 1024, 1024, 2816), ("bf16", 130, 100, 200),
               ("bf16", 256, 128, 128), ("bf16", 640, 384, 384), ("bf16", 2049, 256, 1152),
               ("bf16", 64, 256, 264), ("f32", 130, 70, 200), ("f32", 33, 64, 128), ("f32", 1, 1, 1), ("bf16", 3, 5, 7),
-              ("bf16", 32800, 256, 384)]     # a batch large enough for the down projection's transposed weights
+              ("bf16", 32800, 256, 384), ("bf16", 16384, 256, 256)]   # batches large enough for transposed weights
 
 
 @pytest.mark.parametrize("dtype,M,D,Hd", FFN_SHAPES)
