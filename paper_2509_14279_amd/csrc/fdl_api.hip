@@ -527,6 +527,7 @@ namespace {
 struct ReluPlan {
   int f1_fast, b3_fast, b4_fast, b4_split, f1_wb, b3_wb, b4_wb;
   int f1_wt;               // the forward product (and its recomputation) reads the weights from a transposed copy
+  int g_blocked;           // the masked gradient G lives in 32 x 32 blocks (tuned kernels write and read all of it)
   int64_t b4_fast_rows;
   size_t off_g, off_colpart, off_dwpart, off_xtail, off_wt, bytes;
 };
@@ -551,6 +552,7 @@ bool make_relu_plan(int dt, int64_t M, int64_t K, int64_t N, ReluPlan* q) {
   q->off_xtail = off; off += align256(q->f1_fast ? fast_f1_tail_bytes(M, K) : 0);
   q->f1_wt = q->f1_fast && M >= kTransposeFromRows;
   q->off_wt = off; off += align256(q->f1_wt ? (size_t)N * K * 2 : 0);
+  q->g_blocked = q->f1_fast && q->b3_fast && q->b4_fast && q->b4_fast_rows == M && M % 32 == 0 && N % 32 == 0;
   q->bytes = off;
   return true;
 }
@@ -584,7 +586,7 @@ extern "C" fdl_status fdl_linear_relu_forward(fdl_dtype dt, int64_t M, int64_t K
   if (q.f1_fast) {
     void* Wt = q.f1_wt ? ws + q.off_wt : nullptr;
     if (q.f1_wt) launch_fast_transpose(N, K, W, Wt, s);
-    launch_fast_xwt(1, M, K, N, X, false, W, Wt, b, nullptr, Y, ws + q.off_xtail, s);
+    launch_fast_xwt(1, M, K, N, X, false, W, Wt, b, nullptr, Y, false, ws + q.off_xtail, s);
   } else {
     GemmDesc g = {X, W, M, N, K, K, K, true, true, q.f1_wb};
     launch_generic_xwt((int)dt, 1, g, b, nullptr, Y, s);
@@ -621,14 +623,14 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
   if (p.f1_fast) {
     void* Wt = p.f1_wt ? ws + q.off_wt : nullptr;
     if (p.f1_wt) launch_fast_transpose(N, K, W, Wt, s);
-    launch_fast_xwt(2, M, K, N, X, false, W, Wt, b, dY, G, ws + q.off_xtail, s);
+    launch_fast_xwt(2, M, K, N, X, false, W, Wt, b, dY, G, p.g_blocked != 0, ws + q.off_xtail, s);
   } else {
     GemmDesc g = {X, W, M, N, K, K, K, true, true, p.f1_wb};
     launch_generic_xwt((int)dt, 2, g, b, dY, G, s);
   }
-  launch_colsum((int)dt, M, N, G, colpart, db, s);
+  launch_colsum((int)dt, M, N, G, p.g_blocked != 0, colpart, db, s);
   if (p.b3_fast) {
-    launch_fast_b3(M, K, N, G, false, W, dX, s);
+    launch_fast_b3(M, K, N, G, p.g_blocked != 0, W, dX, s);
   } else {
     GemmDesc g = {G, W, M, K, N, N, K, true, false, p.b3_wb};
     launch_generic_store((int)dt, g, dX, s);
@@ -637,7 +639,7 @@ extern "C" fdl_status fdl_linear_relu_backward(fdl_dtype dt, int64_t M, int64_t 
     const int64_t Mf = p.b4_fast_rows;
     const int extra = Mf < M ? 1 : 0;
     float* dwpart = reinterpret_cast<float*>(ws + q.off_dwpart);
-    launch_fast_b4(Mf, K, N, p.b4_split, extra, G, false, X, dW, dwpart, s);
+    launch_fast_b4(Mf, K, N, p.b4_split, extra, G, p.g_blocked != 0, X, dW, dwpart, s);
     if (extra) {
       const char* Gt = static_cast<const char*>(G) + (size_t)Mf * N * 2;
       const char* Xt = static_cast<const char*>(X) + (size_t)Mf * K * 2;
@@ -750,8 +752,8 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
     if (q.gate_wt) launch_fast_transpose_gate(H, D, Wg, Wu, Wcat, s);
     launch_fast_gate(M, D, H, X, Wg, Wu, Wcat, G, ws + q.off_xtail, s);
   } else if (q.up_fast) {
-    launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, nullptr, G, ws + q.off_xtail, s);
-    launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, nullptr, U, ws + q.off_xtail, s);
+    launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, nullptr, G, false, ws + q.off_xtail, s);
+    launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, nullptr, U, false, ws + q.off_xtail, s);
   } else {
     GemmDesc g = {X, Wg, M, H, D, D, D, true, true, q.up_wb};
     launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, G, s);
@@ -762,7 +764,7 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   if (q.down_fast) {
     void* Wt = q.down_wt ? ws + q.off_wt : nullptr;
     if (q.down_wt) launch_fast_transpose(D, H, Wd, Wt, s);
-    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, Wt, nullptr, nullptr, Y, nullptr, s);
+    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, Wt, nullptr, nullptr, Y, false, nullptr, s);
   } else {
     GemmDesc g = {G, Wd, M, D, H, H, H, true, true, q.down_wb};
     launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, Y, s);

@@ -85,6 +85,7 @@ struct FastParams {
   int split;
   int xcds;              // accelerator dies the workgroup ids are dealt over (1: no die-aware tile order)
   int qblocked;          // 1: Q (the library's own dZ buffer, ldq columns) is stored in blocks of 32 x 32, see Loader
+  int cblocked;          // 1: the output C [J][I] is written in that blocked layout (EPI_MASK: the masked gradient)
 };
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -544,6 +545,13 @@ __device__ __forceinline__ void gemm_tile_loop(const FastParams& p, char* smem, 
       for (int it = 0; it < 8; it++) {
         const u32x4 v = *(const lds_u32x4*)(wtile + roff[it & 3] + (it >> 2) * 4096);
         u32x4* dst = reinterpret_cast<u32x4*>(cbase + (int64_t)(it * 4) * p.I * 2 + svoff);
+        if (EPI == EPI_MASK && p.cblocked) {
+          // row R0 + lane/16 (R0 a multiple of 4, so the four rows share a block row), columns col .. col + 7:
+          // four rows x 64 bytes of each of the four blocks = 256 contiguous bytes per block
+          const int64_t R0 = j0 + wj * 128 + b * 32 + it * 4;
+          const int col = i0 + wi * 128 + e_m * 8;
+          dst = reinterpret_cast<u32x4*>(p.C + (((R0 >> 5) * (p.I >> 5) + (col >> 5)) << 10) + (((R0 & 31) + e_rq) << 5) + (col & 31));
+        }
         if (RAG && j0 + wj * 128 + b * 32 + it * 4 + e_rq >= p.J) continue;   // a row past the end
         if (CRAG && i0 + wi * 128 + e_m * 8 >= p.I) continue;                  // 8 columns past the end
         if (EPI == EPI_MASK) {
@@ -958,9 +966,12 @@ void launch_fast_f1_padded(int64_t M, int64_t K, int64_t N, const void* X, const
 //   kind 2: aux[m][n] where the sum is positive, else 0
 // xtail: fast_f1_tail_bytes(M, K) bytes of scratch when M is not a multiple of 256, unless X itself has readable rows
 // up to the next multiple of 256 (x_padded).  Wt: null, or W^T [K][N] from launch_fast_transpose.
+// out_blocked (kind 2 only; M, N multiples of 32): out is written in 32 x 32 blocks, as the dX and dW kernels read it best.
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
-                     const void* Wt, const float* bias, const void* aux, void* out, void* xtail, hipStream_t s) {
+                     const void* Wt, const float* bias, const void* aux, void* out, bool out_blocked, void* xtail,
+                     hipStream_t s) {
   FastParams p = {};
+  p.cblocked = (out_blocked && kind == 2) ? 1 : 0;
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)X; p.ldp = K; p.ldq = K;
   p.C = (bf16_t*)out; p.bias = bias; p.aux = (const bf16_t*)aux;
   p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);

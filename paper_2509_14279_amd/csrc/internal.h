@@ -143,7 +143,8 @@ void launch_layernorm(int dt, int64_t M, int64_t N, float eps, const void* A, co
                       void* Y, float* mean, float* rstd, hipStream_t s);
 void launch_rmsnorm(int dt, int64_t M, int64_t N, float eps, const void* A, const float* weight, void* Y, hipStream_t s);
 int colsum_groups(int64_t M);
-void launch_colsum(int dt, int64_t M, int64_t N, const void* G, void* colpart, float* out, hipStream_t s);
+// blocked: G is stored in 32 x 32 blocks (bf16; M, N multiples of 32)
+void launch_colsum(int dt, int64_t M, int64_t N, const void* G, bool blocked, void* colpart, float* out, hipStream_t s);
 void launch_silu_mul(int dt, int64_t n, const void* G, const void* U, void* H, hipStream_t s);
 
 // ---- bf16 fast path -----------------------------------------------------------------------------
@@ -174,7 +175,8 @@ void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const voi
 // Wt: null, or the transposed weights from launch_fast_transpose
 constexpr int64_t kTransposeFromRows = 16384;   // batch size from which transposing the weights first pays
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
-                     const void* Wt, const float* bias, const void* aux, void* out, void* xtail, hipStream_t s);
+                     const void* Wt, const float* bias, const void* aux, void* out, bool out_blocked, void* xtail,
+                     hipStream_t s);
 // gate and up products of the feed-forward block with the gated activation in the epilogue (see gemm_bf16.hip)
 bool fast_gate_supported(int64_t M, int64_t D, int64_t H);
 // Wcat: null, or the interleaved transposed weights [D][2H] from launch_fast_transpose_gate

@@ -652,7 +652,9 @@ __global__ __launch_bounds__(256) void norm_wg_kernel(int64_t M, int64_t N, floa
 
 // Column sums of a row-major matrix, first stage: workgroup g sums rows g, g + G, ... of a strip of 256 V columns
 // into colpart[g][N] (arithmetic type); b2_kernel finishes them.  Coalesced along the row, no atomics.
-template <class T, int V>
+// BLK: the matrix is stored in 32 x 32 blocks (see gemm_bf16.hip); a lane's 16 bytes are then a quarter of a 64-byte
+// piece, and the group walks rows in neighbouring pairs, whose pieces share a line (M even).
+template <class T, int V, bool BLK = false>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t M, int64_t N, int strips, int groups,
                                                              const T* __restrict__ G,
                                                              typename ComputeOf<T>::type* __restrict__ colpart) {
@@ -664,12 +666,25 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(int64_t M, int64_t 
   C acc[V];
 #pragma unroll
   for (int v = 0; v < V; v++) acc[v] = 0;
-#pragma unroll 4
-  for (int64_t r = grp; r < M; r += groups) {
-    C x[V];
-    VecIO<T, V>::load(G + r * N + col, x);
+  if constexpr (BLK) {
+    const int64_t cb = ((col >> 5) << 10) + (col & 31);
+#pragma unroll 2
+    for (int64_t r = 2 * (int64_t)grp; r < M; r += 2 * (int64_t)groups) {
+      const T* base = G + (((r >> 5) * (N >> 5)) << 10) + ((r & 31) << 5) + cb;
+      C x[V], y[V];
+      VecIO<T, V>::load(base, x);
+      VecIO<T, V>::load(base + 32, y);     // row r + 1 (r is even: same block row)
 #pragma unroll
-    for (int v = 0; v < V; v++) acc[v] += x[v];
+      for (int v = 0; v < V; v++) acc[v] += x[v] + y[v];
+    }
+  } else {
+#pragma unroll 4
+    for (int64_t r = grp; r < M; r += groups) {
+      C x[V];
+      VecIO<T, V>::load(G + r * N + col, x);
+#pragma unroll
+      for (int v = 0; v < V; v++) acc[v] += x[v];
+    }
   }
 #pragma unroll
   for (int v = 0; v < V; v++) colpart[(int64_t)grp * N + col + v] = acc[v];
@@ -879,7 +894,7 @@ void launch_rmsnorm(int dt, int64_t M, int64_t N, float eps, const void* A, cons
 int colsum_groups(int64_t M) { return (int)(M < 256 ? (M > 0 ? M : 1) : 256); }
 
 // out[j] = sum_i G[i][j]; colpart: colsum_groups(M) * N values of the arithmetic type
-void launch_colsum(int dt, int64_t M, int64_t N, const void* G, void* colpart, float* out, hipStream_t s) {
+void launch_colsum(int dt, int64_t M, int64_t N, const void* G, bool blocked, void* colpart, float* out, hipStream_t s) {
   const int groups = colsum_groups(M);
   const int vmax = dt == kF32 ? 4 : 8;
   const bool vec = N % vmax == 0 && (uintptr_t)G % 16 == 0;
@@ -891,7 +906,8 @@ void launch_colsum(int dt, int64_t M, int64_t N, const void* G, void* colpart, f
     else hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), grid, dim3(256), 0, s, M, N, strips, groups, (const float*)G, (double*)colpart);
     hipLaunchKernelGGL((b2_kernel<double>), dim3((unsigned)((N + 63) / 64), 1), dim3(1024), 0, s, N, groups, (const double*)colpart, out, out, out);
   } else {
-    if (vec) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 8>), grid, dim3(256), 0, s, M, N, strips, groups, (const bf16_t*)G, (float*)colpart);
+    if (vec && blocked) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 8, true>), grid, dim3(256), 0, s, M, N, strips, groups, (const bf16_t*)G, (float*)colpart);
+    else if (vec) hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 8>), grid, dim3(256), 0, s, M, N, strips, groups, (const bf16_t*)G, (float*)colpart);
     else hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 1>), grid, dim3(256), 0, s, M, N, strips, groups, (const bf16_t*)G, (float*)colpart);
     hipLaunchKernelGGL((b2_kernel<float>), dim3((unsigned)((N + 63) / 64), 1), dim3(1024), 0, s, N, groups, (const float*)colpart, out, out, out);
   }
