@@ -697,6 +697,7 @@ struct FfnPlan {
   int up_fast, down_fast, up_wb, down_wb;
   int down_wt;             // the down projection reads its weights from a transposed copy
   int gate_wt;             // the fused gate/up kernel reads both weight matrices from one interleaved transposed copy
+  int g_blocked;           // the gated activation passes from the fused kernel to the down projection in 32 x 32 blocks
   size_t off_g, off_u, off_xtail, off_wt, off_wcat, bytes;
 };
 bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
@@ -720,6 +721,7 @@ bool make_ffn_plan(int dt, int64_t M, int64_t D, int64_t H, FfnPlan* q) {
   q->off_wt = off; off += align256(q->down_wt ? (size_t)D * H * 2 : 0);
   q->gate_wt = q->gate_fused && M >= kTransposeFromRows && H % 64 == 0 && D % 64 == 0;
   q->off_wcat = off; off += align256(q->gate_wt ? (size_t)2 * D * H * 2 : 0);
+  q->g_blocked = q->gate_fused && q->down_wt && H % 32 == 0;
   q->bytes = off;
   return true;
 }
@@ -750,7 +752,7 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   if (q.gate_fused) {
     void* Wcat = q.gate_wt ? ws + q.off_wcat : nullptr;
     if (q.gate_wt) launch_fast_transpose_gate(H, D, Wg, Wu, Wcat, s);
-    launch_fast_gate(M, D, H, X, Wg, Wu, Wcat, G, ws + q.off_xtail, s);
+    launch_fast_gate(M, D, H, X, Wg, Wu, Wcat, G, q.g_blocked != 0, ws + q.off_xtail, s);
   } else if (q.up_fast) {
     launch_fast_xwt(0, M, D, H, X, false, Wg, nullptr, nullptr, nullptr, G, false, ws + q.off_xtail, s);
     launch_fast_xwt(0, M, D, H, X, false, Wu, nullptr, nullptr, nullptr, U, false, ws + q.off_xtail, s);
@@ -764,7 +766,7 @@ extern "C" fdl_status fdl_llama_ffn_forward(fdl_dtype dt, int64_t M, int64_t D, 
   if (q.down_fast) {
     void* Wt = q.down_wt ? ws + q.off_wt : nullptr;
     if (q.down_wt) launch_fast_transpose(D, H, Wd, Wt, s);
-    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, Wt, nullptr, nullptr, Y, false, nullptr, s);
+    launch_fast_xwt(0, M, H, D, G, /*x_padded=*/true, Wd, Wt, nullptr, nullptr, Y, false, nullptr, s, q.g_blocked != 0);
   } else {
     GemmDesc g = {G, Wd, M, D, H, H, H, true, true, q.down_wb};
     launch_generic_xwt((int)dt, 0, g, nullptr, nullptr, Y, s);

@@ -85,7 +85,8 @@ struct FastParams {
   int split;
   int xcds;              // accelerator dies the workgroup ids are dealt over (1: no die-aware tile order)
   int qblocked;          // 1: Q (the library's own dZ buffer, ldq columns) is stored in blocks of 32 x 32, see Loader
-  int cblocked;          // 1: the output C [J][I] is written in that blocked layout (EPI_MASK: the masked gradient)
+  int cblocked;          // 1: the output C [J][I] is written in that blocked layout (EPI_MASK: the masked gradient;
+                         //    EPI_GATE: the gated activation)
 };
 
 typedef __attribute__((address_space(3))) char lds_char;
@@ -601,6 +602,13 @@ __device__ __forceinline__ void gemm_tile_loop(const FastParams& p, char* smem, 
           const int row = it * 8 + g_rq;
           const u32x4 v = *(const lds_u32x4*)(wtile + row * 256 + ((g_m ^ (row & 15)) << 4));
           if (RAG && j0 + wj * 128 + b * 32 + row >= p.J) continue;   // a row past the end
+          if (p.cblocked) {
+            // blocked output (the down projection reads it best that way): row R of the matrix, columns col .. col + 7
+            const int64_t R = j0 + wj * 128 + b * 32 + row;
+            const int col = h0 + g_m * 8;
+            *reinterpret_cast<u32x4*>(p.C + (((R >> 5) * (p.I >> 5) + (col >> 5)) << 10) + ((R & 31) << 5) + (col & 31)) = v;
+            continue;
+          }
           *reinterpret_cast<u32x4*>(cbase + ((int64_t)row * p.I + g_m * 8) * 2) = v;
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -969,9 +977,10 @@ void launch_fast_f1_padded(int64_t M, int64_t K, int64_t N, const void* X, const
 // out_blocked (kind 2 only; M, N multiples of 32): out is written in 32 x 32 blocks, as the dX and dW kernels read it best.
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
                      const void* Wt, const float* bias, const void* aux, void* out, bool out_blocked, void* xtail,
-                     hipStream_t s) {
+                     hipStream_t s, bool x_blocked) {
   FastParams p = {};
   p.cblocked = (out_blocked && kind == 2) ? 1 : 0;
+  p.qblocked = (x_blocked && Wt != nullptr) ? 1 : 0;   // only the transposed-weight kernels read a blocked X
   p.P = (const bf16_t*)W; p.Q = (const bf16_t*)X; p.ldp = K; p.ldq = K;
   p.C = (bf16_t*)out; p.bias = bias; p.aux = (const bf16_t*)aux;
   p.I = (int)N; p.J = (int)M; p.tiles_i = (int)(N / kTile); p.tiles_j = (int)((M + kTile - 1) / kTile);
@@ -1018,8 +1027,9 @@ bool fast_gate_supported(int64_t M, int64_t D, int64_t H) {
          M <= (1 << 24) && (H / 128) * tj <= (1 << 30);
 }
 void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, const void* Wcat,
-                      void* Hout, void* xtail, hipStream_t s) {
+                      void* Hout, bool out_blocked, void* xtail, hipStream_t s) {
   FastParams p = {};
+  p.cblocked = out_blocked ? 1 : 0;    // H a multiple of 32; rows past M are not stored
   p.P = (const bf16_t*)Wg; p.P2 = (const bf16_t*)Wu; p.Q = (const bf16_t*)X; p.ldp = D; p.ldq = D;
   p.C = (bf16_t*)Hout;
   p.I = (int)H; p.J = (int)M; p.tiles_i = (int)(H / 128); p.tiles_j = (int)((M + kTile - 1) / kTile);

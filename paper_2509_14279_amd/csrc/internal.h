@@ -176,13 +176,13 @@ void launch_fast_b4_padded(int64_t M, int64_t K, int64_t N, int split, const voi
 constexpr int64_t kTransposeFromRows = 16384;   // batch size from which transposing the weights first pays
 void launch_fast_xwt(int kind, int64_t M, int64_t K, int64_t N, const void* X, bool x_padded, const void* W,
                      const void* Wt, const float* bias, const void* aux, void* out, bool out_blocked, void* xtail,
-                     hipStream_t s);
+                     hipStream_t s, bool x_blocked = false);   // x_blocked: X in 32 x 32 blocks (needs Wt, x_padded)
 // gate and up products of the feed-forward block with the gated activation in the epilogue (see gemm_bf16.hip)
 bool fast_gate_supported(int64_t M, int64_t D, int64_t H);
 // Wcat: null, or the interleaved transposed weights [D][2H] from launch_fast_transpose_gate
 void launch_fast_transpose_gate(int64_t H, int64_t D, const void* Wg, const void* Wu, void* Wcat, hipStream_t s);
 void launch_fast_gate(int64_t M, int64_t D, int64_t H, const void* X, const void* Wg, const void* Wu, const void* Wcat,
-                      void* Hout, void* xtail, hipStream_t s);
+                      void* Hout, bool out_blocked, void* xtail, hipStream_t s);
 // dZ must have readable rows up to the next multiple of 256
 // dz_blocked: dZ is stored in 32 x 32 blocks (launch_b1_fused with blocked = true; M, N multiples of 32)
 void launch_fast_b3(int64_t M, int64_t K, int64_t N, const void* dZ, bool dz_blocked, const void* W, void* dX,
