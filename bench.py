@@ -9,7 +9,7 @@ and the fp64 oracle timed on the host cores on a bounded sample of the same work
 
 Timing: W untimed warm-up steps, then K steps under the wall clock with device synchronisation on both sides and
 nothing but the two calls inside the loop (`value`); the per-step minimum comes from a second pass with one event
-between steps (`ms_per_step_min`) and the per-phase times from a third with HIP events around every phase (`phases`).  The machine's own ceilings (a register-resident MFMA
+between steps (`ms_per_step_min`), the per-phase times from a third with HIP events around every phase (`phases`), and the step replayed from a HIP graph in a fourth (`ms_per_step_hip_graph`, context).  The machine's own ceilings (a register-resident MFMA
 loop, streaming kernels) are measured in the same process after the timed region and reported next to the
 published peaks (`measured_peak`, `frac_of_measured`, `frac_measured`).
 
@@ -615,6 +615,32 @@ def main():
         for e in s:
             ev.destroy(e)
 
+    # ---- fourth pass (not part of `value`): the same step captured once in a HIP graph and replayed - what a caller
+    # saves who captures the launch sequence (the library allocates nothing and uses no memsets, so it can)
+    graph_ms = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        gstep = lambda: (api.fdl_forward(cfg.dtype, d["X"], d["W"], d["b"], d["gamma"], d["beta"], cfg.eps, Y, Z, mean, rstd, ws, side),
+                         api.fdl_backward(cfg.dtype, d["dY"], d["X"], d["W"], d["gamma"], Z, mean, rstd, dX, dW, db, dg, dbt, ws, side))
+        with torch.cuda.stream(side):
+            gstep()
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            gstep()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / args.steps
+        del graph
+    except Exception:   # context only: never fail the benchmark on it
+        graph_ms = None
+
     # ---- the machine's own ceilings, measured now on this GPU
     ceil = None
     mkey = "mfma_bf16_TFLOP/s" if cfg.dtype == "bf16" else "mfma_f64_TFLOP/s"
@@ -668,6 +694,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "us_per_step": round(ms_per_step * 1e3, 1),
         "ms_per_step_min": round(min(step_ms), 4), "ms_per_step_mean_event_pass": round(sum(step_ms) / len(step_ms), 4),
+        "ms_per_step_hip_graph": None if graph_ms is None else round(graph_ms, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f64",
         "data": "synthetic",
